@@ -1,0 +1,53 @@
+"""The five named workload configurations (shapes, blocks, rho, schedule)."""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+
+@dataclass(frozen=True)
+class WorkloadConfig:
+    name: str
+    config_id: int
+    B: int
+    Hq: int
+    Hkv: int
+    L: int
+    d: int
+    dtype: str            # "bf16" or "f32"
+    bq: int               # query-block rows
+    bk: int               # key-block columns
+    rho: float            # kept fraction of key blocks per query block
+    T: int                # denoising steps in the schedule (1 = single calls)
+    n_dense: int          # steps run with full attention (selection at the last of them)
+    sigma: float          # per-step random-walk std on Q, K, V
+    planted: bool         # head-specific planted structure (False: plain N(0,1), no 1/sqrt(d))
+
+    @property
+    def nqb(self) -> int:
+        return self.L // self.bq
+
+    @property
+    def nkb(self) -> int:
+        return self.L // self.bk
+
+    def scaled(self, **kw) -> "WorkloadConfig":
+        """Same recipe at other sizes (used by tests to shrink a config)."""
+        return replace(self, **kw)
+
+
+CONFIGS = {
+    # Tiny fp32 case the oracle finishes instantly: 1 dense step (selection on it), 4 sparse steps.
+    "tiny": WorkloadConfig("tiny", 1, 1, 2, 2, 256, 64, "f32", 32, 32, 0.3, 5, 1, 0.05, False),
+    # LLaDA-8B-shaped single layer.
+    "llada4k": WorkloadConfig("llada4k", 2, 1, 32, 32, 4096, 128, "bf16", 64, 64, 0.2, 1, 1, 0.0, True),
+    # Same generator at 16k with a 64-step schedule: 8 dense, select once, 56 sparse.
+    "llada16k": WorkloadConfig("llada16k", 3, 1, 32, 32, 16384, 128, "bf16", 64, 64, 0.1, 64, 8, 0.05, True),
+    # Dream-7B-shaped GQA layer: 28 query heads over 4 KV heads.
+    "dream32k": WorkloadConfig("dream32k", 4, 1, 28, 4, 32768, 128, "bf16", 128, 64, 0.1, 1, 1, 0.0, True),
+    # Long-context schedule: 1024 steps, dense for the first 20 %.
+    "long64k": WorkloadConfig("long64k", 5, 1, 32, 32, 65536, 128, "bf16", 128, 64, 0.05, 1024, 205, 0.02, True),
+}
+
+
+def get_config(name: str) -> WorkloadConfig:
+    return CONFIGS[name]
