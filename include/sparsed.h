@@ -1,0 +1,179 @@
+/*
+ * sparsed.h - C ABI of the MI355X (gfx950) SparseD attention library.
+ *
+ * SparseD (arXiv 2509.24014) runs full bidirectional attention for the early
+ * denoising steps of a diffusion language model, selects one block-sparse
+ * pattern per head at a switch step, and reuses it for every later step
+ * (Section 3.3, Algorithm 1). The three calls of that algorithm are the three
+ * compute entry points below. Plain C11: no C++ or framework types cross this
+ * boundary.
+ *
+ * Conventions for every entry point
+ *  - All tensor, index and workspace pointers are DEVICE pointers owned by the
+ *    caller. The library never frees them and keeps no reference after a call
+ *    returns. Descriptor structs themselves live in HOST memory.
+ *  - Work is enqueued on `ex->stream` (a hipStream_t; NULL or ex == NULL means
+ *    the default stream) and the call returns without synchronising, except
+ *    where a function says it synchronises.
+ *  - Errors are returned as a sparsed_status; nothing throws or aborts. On any
+ *    status other than SPARSED_OK no kernel was launched and outputs are
+ *    untouched. sparsed_last_error() gives a thread-local message.
+ *  - Tensors are [B, H, L, D] views with arbitrary element strides for B, H, L
+ *    and unit stride for D. `data` must be 16-byte aligned and every stride a
+ *    multiple of 8 elements (bf16) or 4 elements (fp32), so that every row is
+ *    16-byte aligned.
+ *  - Grouped-query attention: q has Hq heads, k and v have Hkv heads with
+ *    Hq % Hkv == 0; query head h reads key/value head h / (Hq / Hkv).
+ *  - Supported shapes: D in {64, 128}; L a multiple of 64 (bf16) or 32 (fp32);
+ *    block_q in {32, 64, 128}; block_k == 64 for bf16, block_k in {32, 64} for
+ *    fp32; L a multiple of block_q and block_k where blocks are involved.
+ *  - Arithmetic: bf16 tensors are multiplied on the bf16 matrix cores with
+ *    fp32 accumulation, softmax in fp32, probabilities rounded to bf16 before
+ *    the product with V. fp32 tensors use fp32 matrix cores throughout.
+ *    Pooled scores for selection are fp32 from the logits on, for either dtype.
+ */
+#ifndef SPARSED_H
+#define SPARSED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sparsed_status {
+  SPARSED_OK = 0,
+  SPARSED_ERR_NULL = 1,        /* a required pointer is NULL */
+  SPARSED_ERR_SHAPE = 2,       /* dimensions disagree or are not block multiples */
+  SPARSED_ERR_DTYPE = 3,       /* unknown dtype or dtypes differ between tensors */
+  SPARSED_ERR_STRIDE = 4,      /* misaligned pointer or stride */
+  SPARSED_ERR_RANGE = 5,       /* rho outside (0, 1], negative size, ... */
+  SPARSED_ERR_UNSUPPORTED = 6, /* head dim / block size the kernels do not cover */
+  SPARSED_ERR_WORKSPACE = 7,   /* workspace missing or too small */
+  SPARSED_ERR_INDEX = 8,       /* malformed block index */
+  SPARSED_ERR_HIP = 9          /* a HIP runtime call failed; see sparsed_last_error() */
+} sparsed_status;
+
+typedef enum sparsed_dtype { SPARSED_BF16 = 0, SPARSED_F32 = 1 } sparsed_dtype;
+
+/* A [B, H, L, D] view of device memory. Strides are in elements. */
+typedef struct sparsed_tensor {
+  void* data;
+  int32_t dtype; /* sparsed_dtype */
+  int32_t B, H, L, D;
+  int64_t stride_b, stride_h, stride_l;
+} sparsed_tensor;
+
+/*
+ * The sparse pattern M_S of Eq. 4 stored as a per-head CSR over key blocks:
+ * query block I of head (b, h) attends to key blocks
+ *   col_idx[(b*H + h)*cap_per_head + t],  t in [row_ptr[(b*H+h)*(nqb+1) + I],
+ *                                               row_ptr[(b*H+h)*(nqb+1) + I + 1])
+ * i.e. offsets in row_ptr are local to the head's slab and row_ptr[.., 0] == 0.
+ * Each row is strictly ascending. H is the number of QUERY heads. Rows may have
+ * different lengths; an empty row makes that query block's output all zeros.
+ */
+typedef struct sparsed_block_index {
+  int32_t B, H, nqb, nkb;
+  int32_t block_q, block_k;
+  int32_t cap_per_head; /* entries of col_idx reserved per (b, h) */
+  int32_t* row_ptr;     /* device, [B, H, nqb + 1] */
+  int32_t* col_idx;     /* device, [B, H, cap_per_head] */
+} sparsed_block_index;
+
+/* Optional execution context. A NULL context means: default stream, no extras. */
+typedef struct sparsed_exec {
+  void* stream;           /* hipStream_t */
+  void* workspace;        /* device scratch for sparsed_select_pattern, 256-byte aligned */
+  size_t workspace_bytes; /* its size */
+  float* lse_out;         /* attn_dense: optional [B, Hq, L] fp32, log-sum-exp of each row's scaled logits */
+  const float* lse_in;    /* select_pattern: optional [B, Hq, L] fp32 from attn_dense on the SAME q, k */
+  float* pooled_out;      /* select_pattern: optional [B, Hq, nqb, nkb] fp32 copy of the pooled scores A' */
+} sparsed_exec;
+
+/*
+ * Full attention of the early denoising steps (Section 3.1, Eq. 1; Algorithm 1,
+ * the "Skipping Sparse" branch):
+ *     out[b,h,i,:] = sum_j softmax_j(q[b,h,i,:] . k[b,g,j,:] / sqrt(D)) * v[b,g,j,:]
+ * over all j in [0, L), no causal mask. q, out: [B, Hq, L, D]; k, v: [B, Hkv, L, D].
+ * If ex->lse_out is set it also receives log(sum_j exp(logit_ij)) per row.
+ */
+sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor* k,
+                                  const sparsed_tensor* v, sparsed_tensor* out,
+                                  const sparsed_exec* ex);
+
+/*
+ * Pattern selection at the switch step (Section 3.3 "Isolated Selection" with a
+ * single key range, Eq. 6; Algorithm 1, the per-query-block loop):
+ *   1. A' = average of the softmax probabilities A of Eq. 1 over each
+ *      block_q x block_k rectangle (each row of A normalised over all L keys);
+ *   2. for every query block keep the k = sparsed_kept_blocks(rho, nkb) key
+ *      blocks with the largest A' (ties: lower block index), listed ascending.
+ * The L x L matrix A is never formed. Fills out_block_index->row_ptr / col_idx
+ * (every row has exactly k entries, row_ptr[I] = I*k); its B, H, nqb, nkb,
+ * block_q, block_k must already describe q and the blocks and cap_per_head must
+ * be >= nqb*k, else SPARSED_ERR_INDEX. Needs a workspace of
+ * sparsed_select_workspace_bytes(); if ex or ex->workspace is NULL the library
+ * uses a device buffer of its own, allocated (synchronously) on first use and
+ * kept for the life of the process.
+ */
+sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_tensor* k,
+                                      int32_t block_q, int32_t block_k, double rho,
+                                      sparsed_block_index* out_block_index,
+                                      const sparsed_exec* ex);
+
+/*
+ * Sparse attention of the later steps ("Sparse Reusing"; Eq. 3 with the mask of
+ * Eq. 4): rows of query block I attend only to the keys of the key blocks
+ * listed for I; the softmax is normalised over those keys only. The index
+ * contents are trusted (check them with sparsed_index_validate); its shape
+ * fields are checked against q.
+ */
+sparsed_status sparsed_attn_sparse(const sparsed_tensor* q, const sparsed_tensor* k,
+                                   const sparsed_tensor* v, const sparsed_block_index* block_index,
+                                   sparsed_tensor* out, const sparsed_exec* ex);
+
+/*
+ * Isolated selection proper (Section 3.3, Eq. 5 and Eq. 6): key blocks
+ * [0, prefill_blocks) and [prefill_blocks, nkb) are ranked separately, each
+ * keeping sparsed_kept_blocks(rho, size of its range) blocks (none for an empty
+ * range); a row is the ascending union. prefill_blocks == nkb or 0 gives the
+ * same result as sparsed_select_pattern. cap_per_head must be >= nqb * (sum of
+ * the two counts).
+ */
+sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sparsed_tensor* k,
+                                               int32_t block_q, int32_t block_k, double rho,
+                                               int32_t prefill_blocks,
+                                               sparsed_block_index* out_block_index,
+                                               const sparsed_exec* ex);
+
+/* "Top rho%" of n blocks: ceil(rho*n - 1e-9) clamped to [1, n]; 0 if n <= 0. Host only. */
+int32_t sparsed_kept_blocks(double rho, int32_t n);
+
+/*
+ * Number of full-attention steps of a T-step schedule with skip fraction `skip`
+ * (Section 3.3 "Skipping Sparse"): clamp(ceil(T*skip - 1e-9), 1, T). Steps
+ * 0 .. n-1 are dense, the pattern is selected at step n-1, steps n .. T-1 are
+ * sparse. Host only.
+ */
+int32_t sparsed_n_dense_steps(int32_t T, double skip);
+
+/* Bytes of workspace sparsed_select_pattern needs for this q and these blocks (0 on bad arguments). */
+size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);
+
+/*
+ * Checks on the device that every row of the index is in range, strictly
+ * ascending and within cap_per_head. SYNCHRONISES the stream. Returns
+ * SPARSED_ERR_INDEX if any row is malformed.
+ */
+sparsed_status sparsed_index_validate(const sparsed_block_index* idx, const sparsed_exec* ex);
+
+const char* sparsed_status_string(sparsed_status s);
+const char* sparsed_last_error(void); /* thread-local, never NULL */
+int32_t sparsed_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSED_H */

@@ -1,0 +1,16 @@
+"""MI355X-native SparseD attention: Python face of the C-ABI library libsparsed.so."""
+from .binding import (  # noqa: F401
+    BlockIndex,
+    SparsedError,
+    attn_dense,
+    attn_sparse,
+    index_validate,
+    kept_blocks,
+    load_library,
+    n_dense_steps,
+    select_pattern,
+    select_pattern_isolated,
+    select_workspace_bytes,
+    version,
+)
+from .schedule import SparseDLayer  # noqa: F401

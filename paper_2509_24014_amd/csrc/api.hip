@@ -1,0 +1,348 @@
+// Host side of the C ABI declared in include/sparsed.h: argument validation, the "top rho%"
+// count, workspace carving and kernel dispatch. No arithmetic of the method happens here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/sparsed.h"
+#include "kernels.hpp"
+
+using namespace sparsed;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+sparsed_status fail(sparsed_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+sparsed_status hip_fail(hipError_t e, const char* what) {
+  return fail(SPARSED_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+hipStream_t stream_of(const sparsed_exec* ex) { return ex ? static_cast<hipStream_t>(ex->stream) : nullptr; }
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int elem_align(int dtype) { return dtype == SPARSED_BF16 ? 8 : 4; }  // elements per 16 bytes
+
+sparsed_status check_tensor(const sparsed_tensor* t, const char* name) {
+  if (!t) return fail(SPARSED_ERR_NULL, "%s is NULL", name);
+  if (!t->data) return fail(SPARSED_ERR_NULL, "%s.data is NULL", name);
+  if (t->dtype != SPARSED_BF16 && t->dtype != SPARSED_F32) return fail(SPARSED_ERR_DTYPE, "%s: unknown dtype %d", name, t->dtype);
+  if (t->B <= 0 || t->H <= 0 || t->L <= 0 || t->D <= 0)
+    return fail(SPARSED_ERR_SHAPE, "%s: non-positive dimension [%d,%d,%d,%d]", name, t->B, t->H, t->L, t->D);
+  if (t->D != 64 && t->D != 128) return fail(SPARSED_ERR_UNSUPPORTED, "%s: head dim %d not in {64,128}", name, t->D);
+  const int al = elem_align(t->dtype);
+  if (reinterpret_cast<uintptr_t>(t->data) % 16 != 0) return fail(SPARSED_ERR_STRIDE, "%s.data is not 16-byte aligned", name);
+  if (t->stride_l < t->D || t->stride_l % al || t->stride_h % al || t->stride_b % al || t->stride_h < 0 || t->stride_b < 0)
+    return fail(SPARSED_ERR_STRIDE, "%s: strides (%lld,%lld,%lld) must be multiples of %d elements and stride_l >= D", name,
+                (long long)t->stride_b, (long long)t->stride_h, (long long)t->stride_l, al);
+  return SPARSED_OK;
+}
+
+// q: [B,Hq,L,D]; k (and v): [B,Hkv,L,D]; same dtype; Hq % Hkv == 0.
+sparsed_status check_qk(const sparsed_tensor* q, const sparsed_tensor* k, const char* kname) {
+  if (q->dtype != k->dtype) return fail(SPARSED_ERR_DTYPE, "q and %s have different dtypes", kname);
+  if (q->B != k->B || q->L != k->L || q->D != k->D)
+    return fail(SPARSED_ERR_SHAPE, "q [%d,%d,%d,%d] and %s [%d,%d,%d,%d] disagree", q->B, q->H, q->L, q->D, kname, k->B,
+                k->H, k->L, k->D);
+  if (q->H % k->H != 0) return fail(SPARSED_ERR_SHAPE, "query heads %d not a multiple of %s heads %d", q->H, kname, k->H);
+  return SPARSED_OK;
+}
+
+sparsed_status check_out(const sparsed_tensor* q, const sparsed_tensor* out) {
+  if (out->dtype != q->dtype) return fail(SPARSED_ERR_DTYPE, "out and q have different dtypes");
+  if (out->B != q->B || out->H != q->H || out->L != q->L || out->D != q->D) return fail(SPARSED_ERR_SHAPE, "out shape differs from q");
+  return SPARSED_OK;
+}
+
+sparsed_status check_blocks(const sparsed_tensor* q, int bq, int bk) {
+  if (bq != 32 && bq != 64 && bq != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_q %d not in {32,64,128}", bq);
+  if (q->dtype == SPARSED_BF16 && bk != 64) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d: bf16 supports 64", bk);
+  if (q->dtype == SPARSED_F32 && bk != 32 && bk != 64) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64}", bk);
+  if (q->L % bq || q->L % bk) return fail(SPARSED_ERR_SHAPE, "L %d is not a multiple of block_q %d and block_k %d", q->L, bq, bk);
+  return SPARSED_OK;
+}
+
+sparsed_status check_len(const sparsed_tensor* q) {
+  const int m = q->dtype == SPARSED_BF16 ? 64 : 32;
+  if (q->L % m) return fail(SPARSED_ERR_SHAPE, "L %d is not a multiple of %d", q->L, m);
+  return SPARSED_OK;
+}
+
+sparsed_status check_index_shape(const sparsed_block_index* ix, const sparsed_tensor* q) {
+  if (!ix) return fail(SPARSED_ERR_NULL, "block index is NULL");
+  if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
+  if (ix->block_q <= 0 || ix->block_k <= 0) return fail(SPARSED_ERR_INDEX, "block index has non-positive block sizes");
+  if (ix->B != q->B || ix->H != q->H || ix->nqb != q->L / ix->block_q || ix->nkb != q->L / ix->block_k ||
+      q->L % ix->block_q || q->L % ix->block_k)
+    return fail(SPARSED_ERR_INDEX, "block index [B=%d,H=%d,nqb=%d,nkb=%d,%dx%d] does not describe q [%d,%d,%d,%d]", ix->B, ix->H,
+                ix->nqb, ix->nkb, ix->block_q, ix->block_k, q->B, q->H, q->L, q->D);
+  if (ix->cap_per_head < 0) return fail(SPARSED_ERR_INDEX, "negative cap_per_head");
+  return SPARSED_OK;
+}
+
+TensorArg targ(const sparsed_tensor* t) { return TensorArg{t->data, t->stride_b, t->stride_h, t->stride_l}; }
+
+float scale_log2(int D) { return (float)(1.4426950408889634 / std::sqrt((double)D)); }
+
+// Library-owned fallback workspace for callers that pass none: one growing buffer per device.
+std::mutex g_ws_mu;
+void* g_ws[64] = {};
+size_t g_ws_bytes[64] = {};
+
+sparsed_status own_workspace(size_t need, void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return fail(SPARSED_ERR_HIP, "device ordinal %d out of range", dev);
+  std::lock_guard<std::mutex> lk(g_ws_mu);
+  if (g_ws_bytes[dev] < need) {
+    if (g_ws[dev]) {
+      e = hipDeviceSynchronize();  // earlier calls may still be using the old buffer
+      if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+      (void)hipFree(g_ws[dev]);
+      g_ws[dev] = nullptr;
+      g_ws_bytes[dev] = 0;
+    }
+    e = hipMalloc(&g_ws[dev], need);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+    g_ws_bytes[dev] = need;
+  }
+  *out = g_ws[dev];
+  return SPARSED_OK;
+}
+
+size_t select_ws_bytes(int B, int Hq, int L, int nqb, int nkb) {
+  return align256((size_t)B * Hq * L * sizeof(float)) + align256((size_t)B * Hq * nqb * nkb * sizeof(float));
+}
+
+sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tensor* k, const sparsed_tensor* v,
+                         const sparsed_block_index* ix, sparsed_tensor* out, const sparsed_exec* ex) {
+  sparsed_status st;
+  if ((st = check_tensor(q, "q")) || (st = check_tensor(k, "k")) || (st = check_tensor(v, "v")) || (st = check_tensor(out, "out")))
+    return st;
+  if ((st = check_qk(q, k, "k")) || (st = check_qk(q, v, "v")) || (st = check_out(q, out))) return st;
+  if (k->H != v->H) return fail(SPARSED_ERR_SHAPE, "k has %d heads, v has %d", k->H, v->H);
+  if ((st = check_len(q))) return st;
+  AttnArgs a{};
+  a.q = targ(q);
+  a.k = targ(k);
+  a.v = targ(v);
+  a.o = out->data;
+  a.o_sb = out->stride_b;
+  a.o_sh = out->stride_h;
+  a.o_sl = out->stride_l;
+  a.lse = (mode == Mode::kDense && ex) ? ex->lse_out : nullptr;
+  a.B = q->B;
+  a.Hq = q->H;
+  a.Hkv = k->H;
+  a.L = q->L;
+  a.scale_log2 = scale_log2(q->D);
+  int block_q = 0;
+  if (mode == Mode::kSparse) {
+    if ((st = check_index_shape(ix, q))) return st;
+    if ((st = check_blocks(q, ix->block_q, ix->block_k))) return st;
+    a.row_ptr = ix->row_ptr;
+    a.col_idx = ix->col_idx;
+    a.nqb = ix->nqb;
+    a.cap_per_head = ix->cap_per_head;
+    a.block_k = ix->block_k;
+    block_q = ix->block_q;
+  }
+  const hipError_t e = (q->dtype == SPARSED_BF16) ? launch_attn_bf16(mode, q->D, block_q, a, stream_of(ex))
+                                                 : launch_attn_f32(mode, q->D, block_q, a, stream_of(ex));
+  if (e != hipSuccess) return hip_fail(e, mode == Mode::kSparse ? "sparse attention launch" : "dense attention launch");
+  return SPARSED_OK;
+}
+
+sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int32_t bq, int32_t bk, double rho,
+                           int32_t prefill_blocks, bool isolated, sparsed_block_index* ix, const sparsed_exec* ex) {
+  sparsed_status st;
+  if ((st = check_tensor(q, "q")) || (st = check_tensor(k, "k")) || (st = check_qk(q, k, "k"))) return st;
+  if ((st = check_len(q)) || (st = check_blocks(q, bq, bk))) return st;
+  if (!(rho > 0.0) || !(rho <= 1.0)) return fail(SPARSED_ERR_RANGE, "rho %g outside (0, 1]", rho);
+  if ((st = check_index_shape(ix, q))) return st;
+  if (ix->block_q != bq || ix->block_k != bk) return fail(SPARSED_ERR_INDEX, "block index blocks %dx%d differ from %dx%d", ix->block_q, ix->block_k, bq, bk);
+  const int nqb = ix->nqb, nkb = ix->nkb;
+  if (nkb > 8192) return fail(SPARSED_ERR_UNSUPPORTED, "more than 8192 key blocks per row (%d)", nkb);
+  int split = nkb, keep_lo, keep_hi = 0;
+  if (isolated) {
+    if (prefill_blocks < 0 || prefill_blocks > nkb) return fail(SPARSED_ERR_RANGE, "prefill_blocks %d outside [0, %d]", prefill_blocks, nkb);
+    split = prefill_blocks;
+    keep_lo = sparsed_kept_blocks(rho, split);
+    keep_hi = sparsed_kept_blocks(rho, nkb - split);
+  } else {
+    keep_lo = sparsed_kept_blocks(rho, nkb);
+  }
+  const int keep = keep_lo + keep_hi;
+  if ((int64_t)ix->cap_per_head < (int64_t)nqb * keep)
+    return fail(SPARSED_ERR_INDEX, "cap_per_head %d < nqb*k = %lld", ix->cap_per_head, (long long)nqb * keep);
+
+  const size_t lse_bytes = align256((size_t)q->B * q->H * q->L * sizeof(float));
+  const size_t need = select_ws_bytes(q->B, q->H, q->L, nqb, nkb);
+  char* ws = nullptr;
+  if (ex && ex->workspace) {
+    if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ex->workspace_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ex->workspace) % 256) return fail(SPARSED_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    ws = static_cast<char*>(ex->workspace);
+  } else {
+    void* p = nullptr;
+    if ((st = own_workspace(need, &p))) return st;
+    ws = static_cast<char*>(p);
+  }
+  float* lse_buf = reinterpret_cast<float*>(ws);
+  float* apool = (ex && ex->pooled_out) ? ex->pooled_out : reinterpret_cast<float*>(ws + lse_bytes);
+  hipStream_t s = stream_of(ex);
+  const bool bf16 = q->dtype == SPARSED_BF16;
+
+  // 1. row log-sum-exp of Eq. 1's logits, unless the caller passes the one attn_dense produced
+  const float* lse = ex ? ex->lse_in : nullptr;
+  if (!lse) {
+    AttnArgs a{};
+    a.q = targ(q);
+    a.k = targ(k);
+    a.lse = lse_buf;
+    a.B = q->B;
+    a.Hq = q->H;
+    a.Hkv = k->H;
+    a.L = q->L;
+    a.scale_log2 = scale_log2(q->D);
+    const hipError_t e = bf16 ? launch_attn_bf16(Mode::kStats, q->D, 0, a, s) : launch_attn_f32(Mode::kStats, q->D, 0, a, s);
+    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+    lse = lse_buf;
+  }
+  // 2. pooled scores A'
+  PoolArgs p{};
+  p.q = targ(q);
+  p.k = targ(k);
+  p.lse = lse;
+  p.apool = apool;
+  p.B = q->B;
+  p.Hq = q->H;
+  p.Hkv = k->H;
+  p.L = q->L;
+  p.nqb = nqb;
+  p.nkb = nkb;
+  p.block_k = bk;
+  p.scale_log2 = scale_log2(q->D);
+  p.inv_area = 1.0f / ((float)bq * (float)bk);
+  hipError_t e = bf16 ? launch_pool_bf16(q->D, bq, p, s) : launch_pool_f32(q->D, bq, p, s);
+  if (e != hipSuccess) return hip_fail(e, "pooled-score launch");
+  // 3. per-row top-k into the CSR index
+  TopkArgs t{};
+  t.apool = apool;
+  t.row_ptr = ix->row_ptr;
+  t.col_idx = ix->col_idx;
+  t.rows = q->B * q->H * nqb;
+  t.nqb = nqb;
+  t.nkb = nkb;
+  t.split = split;
+  t.keep_lo = keep_lo;
+  t.keep_hi = keep_hi;
+  t.cap_per_head = ix->cap_per_head;
+  e = launch_topk(t, s);
+  if (e != hipSuccess) return hip_fail(e, "top-k launch");
+  return SPARSED_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor* k, const sparsed_tensor* v, sparsed_tensor* out,
+                                  const sparsed_exec* ex) {
+  return attention(Mode::kDense, q, k, v, nullptr, out, ex);
+}
+
+sparsed_status sparsed_attn_sparse(const sparsed_tensor* q, const sparsed_tensor* k, const sparsed_tensor* v,
+                                   const sparsed_block_index* block_index, sparsed_tensor* out, const sparsed_exec* ex) {
+  if (!block_index) return fail(SPARSED_ERR_NULL, "block index is NULL");
+  return attention(Mode::kSparse, q, k, v, block_index, out, ex);
+}
+
+sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q, int32_t block_k, double rho,
+                                      sparsed_block_index* out_block_index, const sparsed_exec* ex) {
+  return select_impl(q, k, block_q, block_k, rho, 0, false, out_block_index, ex);
+}
+
+sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q, int32_t block_k,
+                                               double rho, int32_t prefill_blocks, sparsed_block_index* out_block_index,
+                                               const sparsed_exec* ex) {
+  return select_impl(q, k, block_q, block_k, rho, prefill_blocks, true, out_block_index, ex);
+}
+
+int32_t sparsed_kept_blocks(double rho, int32_t n) {
+  if (n <= 0) return 0;
+  double x = std::ceil(rho * (double)n - 1e-9);
+  if (!(x >= 1.0)) x = 1.0;
+  if (x > (double)n) x = (double)n;
+  return (int32_t)x;
+}
+
+int32_t sparsed_n_dense_steps(int32_t T, double skip) {
+  if (T <= 0) return 0;
+  double x = std::ceil((double)T * skip - 1e-9);
+  if (!(x >= 1.0)) x = 1.0;
+  if (x > (double)T) x = (double)T;
+  return (int32_t)x;
+}
+
+size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
+  if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
+  if (q->L % block_q || q->L % block_k) return 0;
+  return select_ws_bytes(q->B, q->H, q->L, q->L / block_q, q->L / block_k);
+}
+
+sparsed_status sparsed_index_validate(const sparsed_block_index* ix, const sparsed_exec* ex) {
+  if (!ix) return fail(SPARSED_ERR_NULL, "block index is NULL");
+  if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
+  if (ix->B <= 0 || ix->H <= 0 || ix->nqb <= 0 || ix->nkb <= 0 || ix->cap_per_head < 0)
+    return fail(SPARSED_ERR_INDEX, "block index has non-positive dimensions");
+  hipStream_t s = stream_of(ex);
+  int32_t* bad = nullptr;
+  hipError_t e = hipMalloc(&bad, sizeof(int32_t));
+  if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+  int32_t host_bad = 0;
+  e = hipMemcpyAsync(bad, &host_bad, sizeof(int32_t), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) {
+    ValidateArgs a{ix->row_ptr, ix->col_idx, ix->B * ix->H * ix->nqb, ix->nqb, ix->nkb, ix->cap_per_head, bad};
+    e = launch_validate(a, s);
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(&host_bad, bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(bad);
+  if (e != hipSuccess) return hip_fail(e, "index validation");
+  if (host_bad != 0) return fail(SPARSED_ERR_INDEX, "%d malformed rows in the block index", host_bad);
+  return SPARSED_OK;
+}
+
+const char* sparsed_status_string(sparsed_status s) {
+  switch (s) {
+    case SPARSED_OK: return "ok";
+    case SPARSED_ERR_NULL: return "null pointer";
+    case SPARSED_ERR_SHAPE: return "shape mismatch";
+    case SPARSED_ERR_DTYPE: return "dtype mismatch";
+    case SPARSED_ERR_STRIDE: return "bad stride or alignment";
+    case SPARSED_ERR_RANGE: return "argument out of range";
+    case SPARSED_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SPARSED_ERR_WORKSPACE: return "workspace missing or too small";
+    case SPARSED_ERR_INDEX: return "malformed block index";
+    case SPARSED_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* sparsed_last_error(void) { return g_err; }
+
+int32_t sparsed_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Internal interface between the host-side C ABI (api.cpp) and the gfx950 kernels.
+// Not installed; include/sparsed.h is the public boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sparsed {
+
+// One [B, H, L, D] operand: base pointer and element strides (stride of D is 1).
+struct TensorArg {
+  const void* ptr;
+  int64_t sb, sh, sl;
+};
+
+// Arguments of the attention kernels (dense, sparse, and the statistics-only pass).
+struct AttnArgs {
+  TensorArg q, k, v;
+  void* o;
+  int64_t o_sb, o_sh, o_sl;
+  float* lse;              // optional [B, Hq, L]: natural-log sum-exp of each row's scaled logits
+  const int32_t* row_ptr;  // sparse only: [B, Hq, nqb + 1]
+  const int32_t* col_idx;  // sparse only: [B, Hq, cap_per_head]
+  int32_t B, Hq, Hkv, L;
+  int32_t nqb, cap_per_head, block_k;
+  int32_t n_qtiles;        // query tiles per head = L / (rows per work-group)
+  float scale_log2;        // log2(e) / sqrt(D)
+};
+
+// Arguments of the pooled-score kernels (Section 3.3: A' = avgpool(A, block)).
+struct PoolArgs {
+  TensorArg q, k;
+  const float* lse;        // [B, Hq, L] natural-log sum-exp of each row (from the statistics pass)
+  float* apool;            // [B, Hq, nqb, nkb]
+  int32_t B, Hq, Hkv, L;
+  int32_t nqb, nkb, block_k;
+  float scale_log2;        // log2(e) / sqrt(D)
+  float inv_area;          // 1 / (block_q * block_k)
+};
+
+// Arguments of the per-row top-k kernel (Eq. 6): one wavefront per pooled row.
+struct TopkArgs {
+  const float* apool;      // [rows, nkb]
+  int32_t* row_ptr;        // [B*H, nqb + 1]
+  int32_t* col_idx;        // [B*H, cap_per_head]
+  int32_t rows, nqb, nkb;
+  int32_t split;           // key blocks [0, split) and [split, nkb) are ranked separately
+  int32_t keep_lo, keep_hi;  // kept in each range (keep_hi = 0 and split = nkb for one range)
+  int32_t cap_per_head;
+};
+
+struct ValidateArgs {
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  int32_t rows, nqb, nkb, cap_per_head;
+  int32_t* bad;            // device counter of malformed rows
+};
+
+enum class Mode : int { kDense = 0, kSparse = 1, kStats = 2 };
+
+// Launchers. Each returns the HIP error of the launch. block_q selects the work-group shape for
+// the sparse and pooled kernels; dense and stats pick their own query tile from L.
+hipError_t launch_attn_bf16(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s);
+hipError_t launch_attn_f32(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s);
+hipError_t launch_pool_bf16(int D, int block_q, const PoolArgs& a, hipStream_t s);
+hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s);
+hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
+hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);
+hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+
+// Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).
+int dense_qtile_bf16(int L);
+int dense_qtile_f32(int L);
+
+}  // namespace sparsed

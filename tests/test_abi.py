@@ -1,0 +1,95 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and its
+host-only logic (the "top rho%" count, the dense-step count, argument validation) behaves.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from oracle import schedule as oracle_schedule
+from paper_2509_24014_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sparsed.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sparsed_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = _declared_functions()
+    assert "sparsed_attn_dense" in names and "sparsed_select_pattern" in names and "sparsed_attn_sparse" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in sparsed.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+    assert binding.version() >= 100
+
+
+def test_kept_blocks_and_dense_steps_agree_with_the_written_rule():
+    for n in range(0, 70):
+        for pct in range(1, 101):
+            want = max(1, -((-pct * n) // 100)) if n > 0 else 0
+            assert binding.kept_blocks(pct / 100.0, n) == want
+            if n > 0:
+                assert binding.kept_blocks(pct / 100.0, n) == oracle.kept_blocks(pct / 100.0, n)
+    for rho, n, k in [(0.3, 8, 3), (0.2, 64, 13), (0.1, 256, 26), (0.1, 512, 52), (0.05, 1024, 52)]:
+        assert binding.kept_blocks(rho, n) == k
+    for T, skip, nd in [(1024, 0.2, 205), (64, 0.125, 8), (5, 0.2, 1), (10, 0.3, 3), (10, 0.0, 1), (10, 1.0, 10)]:
+        assert binding.n_dense_steps(T, skip) == nd == oracle_schedule.n_dense_steps(T, skip)
+
+
+def _t(B=1, H=2, L=256, D=64, dtype=binding.SPARSED_F32, data=0x1000, sl=None, sh=None, sb=None):
+    sl = D if sl is None else sl
+    sh = L * sl if sh is None else sh
+    sb = H * sh if sb is None else sb
+    return binding._Tensor(data, dtype, B, H, L, D, sb, sh, sl)
+
+
+def _ix(B=1, H=2, nqb=8, nkb=8, bq=32, bk=32, cap=24, rp=0x2000, ci=0x3000):
+    return binding._BlockIndex(B, H, nqb, nkb, bq, bk, cap, rp, ci)
+
+
+def test_argument_validation_rejects_before_any_launch():
+    # every call below fails validation on the host; the fake device pointers are never touched
+    lib = binding.load_library()
+    R = ctypes.byref
+    q, k, v, o = _t(), _t(), _t(), _t()
+    assert lib.sparsed_attn_dense(None, R(k), R(v), R(o), None) == 1                       # NULL
+    assert lib.sparsed_attn_dense(R(_t(data=None)), R(k), R(v), R(o), None) == 1
+    assert lib.sparsed_attn_dense(R(_t(D=96)), R(k), R(v), R(o), None) == 6                # head dim
+    assert lib.sparsed_attn_dense(R(_t(dtype=7)), R(k), R(v), R(o), None) == 3             # dtype
+    assert lib.sparsed_attn_dense(R(q), R(_t(dtype=binding.SPARSED_BF16)), R(v), R(o), None) == 3
+    assert lib.sparsed_attn_dense(R(q), R(_t(L=128)), R(v), R(o), None) == 2               # shapes
+    assert lib.sparsed_attn_dense(R(_t(H=3)), R(k), R(v), R(_t(H=3)), None) == 2           # 3 % 2 != 0
+    assert lib.sparsed_attn_dense(R(_t(data=0x1004)), R(k), R(v), R(o), None) == 4         # alignment
+    assert lib.sparsed_attn_dense(R(_t(sl=66)), R(k), R(v), R(o), None) == 4               # stride
+    assert lib.sparsed_attn_dense(R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), None) == 2   # L % 32
+    assert b"L 48" in lib.sparsed_last_error()
+    ix = _ix()
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.0, R(ix), None) == 5           # rho
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 1.5, R(ix), None) == 5
+    assert lib.sparsed_select_pattern(R(q), R(k), 48, 32, 0.3, R(ix), None) == 6           # block sizes
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(_ix(cap=23)), None) == 8  # capacity < nqb*k
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(_ix(nkb=4)), None) == 8   # index vs q
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, None, None) == 1
+    qb = _t(dtype=binding.SPARSED_BF16, D=128)
+    assert lib.sparsed_select_pattern(R(qb), R(qb), 64, 32, 0.3, R(_ix(nqb=4, nkb=8, bq=64, bk=32)), None) == 6  # bf16 bk
+    ex = binding._Exec(None, 0x4000, 16, None, None, None)
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(ix), R(ex)) == 7          # workspace too small
+    assert lib.sparsed_attn_sparse(R(q), R(k), R(v), None, R(o), None) == 1
+    assert lib.sparsed_attn_sparse(R(q), R(k), R(v), R(_ix(H=4)), R(o), None) == 8
+    assert lib.sparsed_select_pattern_isolated(R(q), R(k), 32, 32, 0.3, 9, R(_ix(cap=64)), None) == 5
+    assert lib.sparsed_status_string(8) == b"malformed block index"
+
+
+def test_workspace_size_formula():
+    lib = binding.load_library()
+    t = _t(B=1, H=32, L=65536, D=128, dtype=binding.SPARSED_BF16)
+    need = lib.sparsed_select_workspace_bytes(ctypes.byref(t), 128, 64)
+    assert need == 32 * 65536 * 4 + 32 * 512 * 1024 * 4
+    assert lib.sparsed_select_workspace_bytes(ctypes.byref(t), 100, 64) == 0

@@ -1,0 +1,384 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element.
+
+Small cases are compared in full; the named full-size workloads are compared on sampled
+(head, query-block) units, which the oracle can compute one by one (every unit depends only on
+its own query rows and its head's K, V)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_24014_amd as sd
+import workload
+from parity_utils import BF16_MAX, assert_output_close, compare_index, random_csr
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _rand_qkv(B, Hq, Hkv, L, D, dtype, seed, scale=None):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    scale = (1.0 / math.sqrt(math.sqrt(D))) if scale is None else scale  # logits ~ N(0, 1)
+    q = (torch.randn(B, Hq, L, D, generator=g) * scale).to(dtype)
+    k = (torch.randn(B, Hkv, L, D, generator=g) * scale).to(dtype)
+    v = torch.randn(B, Hkv, L, D, generator=g).to(dtype)
+    return q, k, v
+
+
+def _dev(*ts):
+    return tuple(t.to(DEV) for t in ts)
+
+
+# ----------------------------------------------------------------------------- dense (Eq. 1)
+@pytest.mark.parametrize("B,Hq,Hkv,L,D", [
+    (1, 2, 2, 256, 128),    # one 256-row work-group per head
+    (2, 4, 2, 320, 128),    # 320 = 5 x 64: the 64-row work-group shape, grouped heads, batch 2
+    (1, 3, 1, 384, 64),     # 128-row work-groups, head dim 64, 3 query heads on one KV head
+    (1, 2, 1, 1024, 128),   # 16 key tiles
+    (1, 1, 1, 64, 128),     # a single tile
+])
+def test_dense_bf16(B, Hq, Hkv, L, D):
+    _say(f"dense bf16 B={B} Hq={Hq} Hkv={Hkv} L={L} D={D}")
+    q, k, v = _rand_qkv(B, Hq, Hkv, L, D, torch.bfloat16, seed=L + D)
+    want = oracle.attn_dense(q, k, v)
+    got = sd.attn_dense(*_dev(q, k, v))
+    torch.cuda.synchronize()
+    assert_output_close(got, want, torch.bfloat16, "dense bf16")
+
+
+def test_dense_bf16_peaked_rows_and_large_logits():
+    # logits spread over +-30: exercises the running-max rescale across tiles
+    q, k, v = _rand_qkv(1, 2, 2, 512, 128, torch.bfloat16, seed=7, scale=0.9)
+    want = oracle.attn_dense(q, k, v)
+    got = sd.attn_dense(*_dev(q, k, v))
+    assert_output_close(got, want, torch.bfloat16, "dense bf16 peaked")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,D", [(1, 2, 2, 256, 64), (1, 2, 1, 96, 128), (2, 2, 2, 192, 64)])
+def test_dense_f32(B, Hq, Hkv, L, D):
+    _say(f"dense f32 B={B} Hq={Hq} Hkv={Hkv} L={L} D={D}")
+    q, k, v = _rand_qkv(B, Hq, Hkv, L, D, torch.float32, seed=L + D, scale=1.0 if D == 64 else None)
+    want = oracle.attn_dense(q, k, v)
+    got = sd.attn_dense(*_dev(q, k, v))
+    assert_output_close(got, want, torch.float32, "dense f32")
+
+
+def test_dense_strided_views_and_preallocated_output():
+    # Q, K, V stored as [B, L, H, D] (the layout a fused QKV projection leaves) and viewed as [B, H, L, D]
+    B, H, L, D = 1, 4, 256, 128
+    g = torch.Generator().manual_seed(3)
+    qkv = (torch.randn(3, B, L, H, D, generator=g) * 0.3).to(torch.bfloat16)
+    q, k, v = (x.transpose(1, 2) for x in qkv)           # non-contiguous views
+    want = oracle.attn_dense(q, k, v)
+    qd, kd, vd = (x.transpose(1, 2) for x in qkv.to(DEV))
+    out = torch.full((B, L, H, D), float("nan"), dtype=torch.bfloat16, device=DEV).transpose(1, 2)
+    ret = sd.attn_dense(qd, kd, vd, out=out)
+    assert ret.data_ptr() == out.data_ptr()
+    assert_output_close(out, want, torch.bfloat16, "dense strided")
+
+
+@pytest.mark.parametrize("dtype,L,D", [(torch.bfloat16, 512, 128), (torch.float32, 256, 64)])
+def test_dense_log_sum_exp_side_output(dtype, L, D):
+    q, k, v = _rand_qkv(1, 2, 1, L, D, dtype, seed=11)
+    lse = torch.empty(1, 2, L, dtype=torch.float32, device=DEV)
+    sd.attn_dense(*_dev(q, k, v), lse_out=lse)
+    logits = q.double() @ k.double().repeat_interleave(2, 1).transpose(-1, -2) / math.sqrt(D)
+    want = torch.logsumexp(logits, dim=-1)
+    assert (lse.cpu().double() - want).abs().max() < 2e-5
+
+
+# ----------------------------------------------------------------------------- sparse (Eq. 3, Eq. 4)
+@pytest.mark.parametrize("bq,L,Hq,Hkv,D", [(128, 1024, 2, 2, 128), (64, 512, 4, 2, 128), (32, 256, 2, 1, 128), (64, 512, 2, 2, 64)])
+def test_sparse_bf16_oracle_index_and_ragged_index(bq, L, Hq, Hkv, D):
+    _say(f"sparse bf16 bq={bq} L={L} Hq={Hq} Hkv={Hkv} D={D}")
+    bk = 64
+    q, k, v = _rand_qkv(1, Hq, Hkv, L, D, torch.bfloat16, seed=bq + L)
+    qd, kd, vd = _dev(q, k, v)
+    # (a) the oracle's own selected pattern
+    row_ptr, col_idx, _, _ = oracle.select_pattern(q, k, bq, bk, 0.3)
+    ix = sd.BlockIndex(torch.from_numpy(row_ptr).to(DEV), torch.from_numpy(col_idx).to(DEV), bq, bk, L // bk)
+    sd.index_validate(ix)
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    assert_output_close(got, oracle.attn_sparse(q, k, v, row_ptr, col_idx, bq, bk), torch.bfloat16, "sparse bf16")
+    # (b) ragged CSR: rows of different lengths, some empty (their output rows must be exactly zero)
+    rp, ci = random_csr(1, Hq, L // bq, L // bk, min(5, L // bk), seed=L, device=DEV)
+    ix = sd.BlockIndex(rp, ci, bq, bk, L // bk)
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    want = oracle.attn_sparse(q, k, v, rp.cpu().numpy(), ci.cpu().numpy(), bq, bk)
+    assert_output_close(got, want, torch.bfloat16, "sparse bf16 ragged")
+    empty = (rp[..., 1:] == rp[..., :-1]).cpu().numpy()
+    assert empty.any()
+    rows_empty = np.repeat(empty, bq, axis=-1)
+    assert (got.cpu().float().numpy()[rows_empty] == 0).all()
+
+
+@pytest.mark.parametrize("bq,bk,L,D", [(32, 32, 256, 64), (64, 64, 256, 64), (128, 32, 256, 128)])
+def test_sparse_f32(bq, bk, L, D):
+    q, k, v = _rand_qkv(1, 2, 2, L, D, torch.float32, seed=bq + bk, scale=1.0 if D == 64 else None)
+    qd, kd, vd = _dev(q, k, v)
+    row_ptr, col_idx, _, _ = oracle.select_pattern(q, k, bq, bk, 0.3)
+    ix = sd.BlockIndex(torch.from_numpy(row_ptr).to(DEV), torch.from_numpy(col_idx).to(DEV), bq, bk, L // bk)
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    assert_output_close(got, oracle.attn_sparse(q, k, v, row_ptr, col_idx, bq, bk), torch.float32, "sparse f32")
+    rp, ci = random_csr(1, 2, L // bq, L // bk, 3, seed=5, device=DEV)
+    got = sd.attn_sparse(qd, kd, vd, sd.BlockIndex(rp, ci, bq, bk, L // bk))
+    want = oracle.attn_sparse(q, k, v, rp.cpu().numpy(), ci.cpu().numpy(), bq, bk)
+    assert_output_close(got, want, torch.float32, "sparse f32 ragged")
+
+
+def test_sparse_with_every_block_listed_equals_dense_kernel_within_rounding():
+    q, k, v = _rand_qkv(1, 2, 2, 512, 128, torch.bfloat16, seed=21)
+    qd, kd, vd = _dev(q, k, v)
+    ix = sd.select_pattern(qd, kd, 128, 64, 1.0)
+    assert ix.col_idx.view(1, 2, 4, 8).cpu().eq(torch.arange(8)).all()
+    a = sd.attn_sparse(qd, kd, vd, ix)
+    want = oracle.attn_dense(q, k, v)
+    assert_output_close(a, want, torch.bfloat16, "sparse rho=1")
+
+
+def test_index_validate_flags_malformed_rows():
+    rp, ci = random_csr(1, 2, 4, 8, 3, seed=1, device=DEV, allow_empty=False)
+    ix = sd.BlockIndex(rp, ci, 64, 64, 8)
+    sd.index_validate(ix)
+    bad = ci.clone()
+    bad[0, 1, 0] = 8                      # out of range
+    with pytest.raises(sd.SparsedError) as e:
+        sd.index_validate(sd.BlockIndex(rp, bad, 64, 64, 8))
+    assert e.value.status == 8
+    bad = ci.clone()
+    n0 = int(rp[0, 0, 1])
+    if n0 >= 2:
+        bad[0, 0, 1] = bad[0, 0, 0]       # not strictly ascending
+        with pytest.raises(sd.SparsedError):
+            sd.index_validate(sd.BlockIndex(rp, bad, 64, 64, 8))
+
+
+# ----------------------------------------------------------------------------- selection (Section 3.3, Eq. 6)
+def _check_selection(q, k, bq, bk, rho, use_lse, what):
+    B, Hq, L, D = q.shape
+    nqb, nkb = L // bq, L // bk
+    qd, kd = _dev(q, k)
+    pooled = torch.empty(B, Hq, nqb, nkb, dtype=torch.float32, device=DEV)
+    lse = None
+    if use_lse:
+        lse = torch.empty(B, Hq, L, dtype=torch.float32, device=DEV)
+        sd.attn_dense(qd, kd, kd, lse_out=lse)   # V is irrelevant for the log-sum-exp
+    ix = sd.select_pattern(qd, kd, bq, bk, rho, lse_in=lse, pooled_out=pooled)
+    sd.index_validate(ix)
+    row_ptr, col_idx, apool, _ = oracle.select_pattern(q, k, bq, bk, rho)
+    keep = oracle.kept_blocks(rho, nkb)
+    np.testing.assert_array_equal(ix.row_ptr.cpu().numpy(), row_ptr)
+    rel = np.abs(pooled.cpu().double().numpy() - apool) / apool
+    assert rel.max() < 5e-6, f"{what}: pooled scores off by {rel.max():.2e} relative"
+    tie_rows, tie_blocks = compare_index(ix.col_idx.cpu().numpy()[..., :nqb * keep], col_idx, apool.reshape(-1, nkb), keep)
+    _say(f"{what}: rows={B * Hq * nqb} keep={keep} tie_rows={tie_rows} tie_blocks={tie_blocks} pooled_rel_err={rel.max():.2e}")
+    return ix
+
+
+@pytest.mark.parametrize("bq,L,Hq,Hkv,D,rho,use_lse", [
+    (128, 1024, 2, 2, 128, 0.25, False), (64, 1024, 4, 2, 128, 0.2, True), (32, 512, 2, 1, 64, 0.3, False),
+    (128, 512, 2, 2, 128, 1.0, False), (64, 512, 2, 2, 128, 0.01, True)])
+def test_select_bf16(bq, L, Hq, Hkv, D, rho, use_lse):
+    q, k, _ = _rand_qkv(1, Hq, Hkv, L, D, torch.bfloat16, seed=bq + L, scale=0.45)
+    _check_selection(q, k, bq, 64, rho, use_lse, f"select bf16 bq={bq} L={L} rho={rho}")
+
+
+@pytest.mark.parametrize("bq,bk,L,D,use_lse", [(32, 32, 256, 64, False), (64, 64, 256, 64, True), (128, 32, 512, 128, False)])
+def test_select_f32(bq, bk, L, D, use_lse):
+    q, k, _ = _rand_qkv(1, 2, 2, L, D, torch.float32, seed=bq + bk, scale=1.0 if D == 64 else 0.45)
+    _check_selection(q, k, bq, bk, 0.3, use_lse, f"select f32 {bq}x{bk} L={L}")
+
+
+def test_select_ties_resolve_to_lower_block_index():
+    # Q = 0 makes every pooled score exactly 1/L: the kept set must be the first k blocks
+    q = torch.zeros(1, 2, 512, 128, dtype=torch.bfloat16)
+    k = torch.randn(1, 2, 512, 128).to(torch.bfloat16)
+    ix = sd.select_pattern(*_dev(q, k), 64, 64, 0.4)
+    keep = oracle.kept_blocks(0.4, 8)
+    assert ix.col_idx.cpu().view(1, 2, 8, keep).eq(torch.arange(keep)).all()
+
+
+def test_select_isolated_matches_oracle():
+    q, k, _ = _rand_qkv(1, 2, 2, 1024, 128, torch.bfloat16, seed=31, scale=0.45)
+    bq, bk, rho, n_pre = 128, 64, 0.25, 6
+    ix = sd.select_pattern_isolated(*_dev(q, k), bq, bk, rho, n_pre)
+    apool = oracle.pool_scores(q, k, bq, bk)
+    rp, ci = oracle.select_isolated(apool, rho, n_pre)
+    np.testing.assert_array_equal(ix.row_ptr.cpu().numpy(), rp)
+    got, want = ix.col_idx.cpu().numpy(), ci
+    keep_pre, keep_gen = oracle.kept_blocks(rho, n_pre), oracle.kept_blocks(rho, 16 - n_pre)
+    g = got.reshape(-1, keep_pre + keep_gen)
+    w = want.reshape(-1, keep_pre + keep_gen)
+    ap = apool.reshape(-1, 16)
+    compare_index(g[:, :keep_pre], w[:, :keep_pre], np.where(np.arange(16) < n_pre, ap, -1.0), keep_pre)
+    gen_scores = np.where(np.arange(16) >= n_pre, ap, -1.0)
+    compare_index(g[:, keep_pre:], w[:, keep_pre:], gen_scores, keep_gen)
+
+
+# ----------------------------------------------------------------------------- closed form W1 on the GPU
+def test_closed_form_w1_embedded_in_head_dim_64():
+    # tests/golden/w1_closed_form.txt, padded to L=64 x d=64: the 4 worked rows/keys are spread so that
+    # each falls in its own 32-block, all other keys get a logit of -60 (weight e^-60), scale sqrt(64)=8 undone on q.
+    from test_oracle_pins import _read_golden
+    g = _read_golden("w1_closed_form.txt")
+    L, D = 128, 64
+    q = torch.zeros(1, 1, L, D)
+    k = torch.zeros(1, 1, L, D)
+    v = torch.zeros(1, 1, L, D)
+    rows = [0, 1, 32, 33]                       # query rows 0,1 in block 0; 2,3 in block 1 (bq = 32)
+    keys = [0, 1, 64, 65]                       # keys 0,1 in key block 0; 2,3 in key block 2 (bk = 32)
+    k[0, 0, :, 1] = -60.0
+    for n, j in enumerate(keys):
+        k[0, 0, j, 0] = math.log(g["w"][n])
+        k[0, 0, j, 1] = 0.0
+        v[0, 0, j, 0] = g["v"][n]
+    q[0, 0, :, 1] = 8.0                         # every query pushes the padding keys to logit -60
+    for n, i in enumerate(rows):
+        q[0, 0, i, 0] = 8.0 * g["q"][n]
+    want = oracle.attn_dense(q, k, v)
+    np.testing.assert_allclose(want[0, 0, rows, 0], g["dense"], atol=1e-6)
+    got = sd.attn_dense(*_dev(q, k, v))
+    np.testing.assert_allclose(got.cpu().double().numpy()[0, 0, rows, 0], g["dense"], atol=1e-5)
+
+
+# ----------------------------------------------------------------------------- the tiny schedule, in full
+def test_tiny_config_full_schedule():
+    cfg = workload.get_config("tiny")
+    _say(f"tiny schedule: T={cfg.T} n_dense={cfg.n_dense}")
+    inp = workload.make_inputs(cfg, seed=0, device="cpu")
+    layer = sd.SparseDLayer(cfg.T, 0.2, cfg.bq, cfg.bk, cfg.rho)
+    assert layer.n_dense == cfg.n_dense == 1
+    ora_index = None
+    for t in range(cfg.T):
+        q, k, v = inp.rounded()
+        got = layer.step(*_dev(q, k, v), t)
+        if t < cfg.n_dense:
+            want = oracle.attn_dense(q, k, v)
+            if t == cfg.n_dense - 1:
+                rp, ci, apool, _ = oracle.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho)
+                keep = oracle.kept_blocks(cfg.rho, cfg.nkb)
+                assert keep == 3
+                ties = compare_index(layer.index.col_idx.cpu().numpy(), ci, apool.reshape(-1, cfg.nkb), keep)
+                _say(f"tiny: ties {ties}")
+                ora_index = (layer.index.row_ptr.cpu().numpy(), layer.index.col_idx.cpu().numpy())
+                frozen = layer.index.col_idx.clone()
+        else:
+            # sparse steps are checked against the oracle run on the SAME (GPU-selected) index
+            want = oracle.attn_sparse(q, k, v, ora_index[0], ora_index[1], cfg.bq, cfg.bk)
+            assert torch.equal(layer.index.col_idx, frozen)      # the pattern is reused, never recomputed
+        assert_output_close(got, want, torch.float32, f"tiny step {t}")
+        inp.advance()
+    assert layer.calls == {"dense": 1, "select": 1, "sparse": 4}
+
+
+# ----------------------------------------------------------------------------- named workloads at full size
+def _sample_units(cfg, n_per_type, seed):
+    """(head, query block) units: every head type, first and last query block always included."""
+    rng = np.random.default_rng(seed)
+    units = []
+    for t in range(4):
+        heads = [h for h in range(cfg.Hq) if h % 4 == t]
+        h = heads[int(rng.integers(len(heads)))]
+        blocks = {0, cfg.nqb - 1}
+        while len(blocks) < n_per_type:
+            blocks.add(int(rng.integers(cfg.nqb)))
+        units += [(h, I) for I in sorted(blocks)]
+    return units
+
+
+def _check_workload_sampled(name, n_per_type, check_dense=True):
+    cfg = workload.get_config(name)
+    _say(f"{name}: generating L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} {cfg.bq}x{cfg.bk} rho={cfg.rho}")
+    inp = workload.make_inputs(cfg, seed=0, device=DEV)
+    q, k, v = inp.rounded()
+    del inp
+    keep = oracle.kept_blocks(cfg.rho, cfg.nkb)
+    lse = torch.empty(cfg.B, cfg.Hq, cfg.L, dtype=torch.float32, device=DEV)
+    dense = sd.attn_dense(q, k, v, lse_out=lse)
+    pooled = torch.empty(cfg.B, cfg.Hq, cfg.nqb, cfg.nkb, dtype=torch.float32, device=DEV)
+    ix = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, lse_in=lse, pooled_out=pooled)
+    ix2 = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho)           # own statistics pass
+    sd.index_validate(ix)
+    sparse = sd.attn_sparse(q, k, v, ix)
+    torch.cuda.synchronize()
+    # properties that hold at any size
+    assert torch.isfinite(dense.float()).all() and torch.isfinite(sparse.float()).all()
+    assert ix.row_ptr.cpu().eq(torch.arange(cfg.nqb + 1, dtype=torch.int32) * keep).all()
+    cols = ix.col_idx.view(cfg.B, cfg.Hq, cfg.nqb, keep)
+    assert (cols[..., 1:] > cols[..., :-1]).all() and cols.min() >= 0 and cols.max() < cfg.nkb
+    np.testing.assert_allclose(pooled.sum(-1).cpu().numpy(), 1.0 / cfg.bk, rtol=2e-5)   # rows of A' sum to 1/bk
+    same = (ix2.col_idx == ix.col_idx).view(cfg.B, cfg.Hq, cfg.nqb, keep).all(-1).float().mean().item()
+    _say(f"{name}: rows identical between lse_in and own-statistics selection: {100 * same:.2f}%")
+    # sampled units against the oracle
+    group = cfg.Hq // cfg.Hkv
+    tie_rows = tie_blocks = 0
+    units = _sample_units(cfg, n_per_type, seed=1)
+    cache = {}
+    for (h, I) in units:
+        if h not in cache:
+            cache.clear()
+            cache[h] = (q[:, h:h + 1].float().cpu(), k[:, h // group:h // group + 1].float().cpu(),
+                        v[:, h // group:h // group + 1].float().cpu())
+        qh, kh, vh = cache[h]
+        r0, r1 = I * cfg.bq, (I + 1) * cfg.bq
+        if check_dense:
+            want = oracle.attn_dense_rows(qh, kh, vh, 0, 0, r0, r1)
+            assert_output_close(dense[0, h, r0:r1], want, torch.bfloat16, f"{name} dense h={h} I={I}")
+        ap = oracle.pool_scores_rows(qh, kh, cfg.bq, cfg.bk, 0, 0, I, I + 1)
+        _, ci, _ = oracle.select_topk(ap.reshape(1, 1, 1, cfg.nkb), keep)
+        tr, tb = compare_index(cols[0, h, I].cpu().numpy(), ci.reshape(-1), ap.reshape(1, cfg.nkb), keep)
+        tie_rows += tr
+        tie_blocks += tb
+        rel = np.abs(pooled[0, h, I].cpu().double().numpy() - ap[0]) / ap[0]
+        assert rel.max() < 2e-5, f"{name} pooled h={h} I={I}: {rel.max():.2e}"
+        # sparse output against the oracle run on the GPU-selected row
+        rp1 = np.zeros((1, 1, cfg.nqb + 1), dtype=np.int32)
+        rp1[0, 0, I + 1:] = keep
+        ci1 = cols[0, h, I].cpu().numpy().reshape(1, 1, keep)
+        want = oracle.attn_sparse_rows(qh, kh, vh, rp1, ci1, cfg.bq, cfg.bk, 0, 0, I, I + 1)
+        assert_output_close(sparse[0, h, r0:r1], want, torch.bfloat16, f"{name} sparse h={h} I={I}")
+        _say(f"{name}: unit h={h} I={I} ok")
+    _say(f"{name}: {len(units)} units checked; tie_rows={tie_rows} tie_blocks={tie_blocks}")
+
+
+def test_workload_llada4k_full_tensor():
+    """The 4k LLaDA-shaped layer, compared in full."""
+    cfg = workload.get_config("llada4k")
+    inp = workload.make_inputs(cfg, seed=0, device=DEV)
+    q, k, v = inp.rounded()
+    qc, kc, vc = q.cpu(), k.cpu(), v.cpu()
+    _say("llada4k: oracle dense")
+    want = oracle.attn_dense(qc, kc, vc)
+    lse = torch.empty(cfg.B, cfg.Hq, cfg.L, dtype=torch.float32, device=DEV)
+    got = sd.attn_dense(q, k, v, lse_out=lse)
+    assert_output_close(got, want, torch.bfloat16, "llada4k dense")
+    _say("llada4k: oracle selection")
+    rp, ci, apool, _ = oracle.select_pattern(qc, kc, cfg.bq, cfg.bk, cfg.rho)
+    ix = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, lse_in=lse)
+    keep = oracle.kept_blocks(cfg.rho, cfg.nkb)
+    assert keep == 13
+    tr, tb = compare_index(ix.col_idx.cpu().numpy(), ci, apool.reshape(-1, cfg.nkb), keep)
+    _say(f"llada4k: selection rows={cfg.Hq * cfg.nqb} tie_rows={tr} tie_blocks={tb}")
+    _say("llada4k: oracle sparse (on the GPU-selected index)")
+    want = oracle.attn_sparse(qc, kc, vc, ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy(), cfg.bq, cfg.bk)
+    got = sd.attn_sparse(q, k, v, ix)
+    assert_output_close(got, want, torch.bfloat16, "llada4k sparse")
+
+
+def test_workload_llada16k_sampled():
+    _check_workload_sampled("llada16k", n_per_type=3)
+
+
+def test_workload_dream32k_gqa_sampled():
+    _check_workload_sampled("dream32k", n_per_type=3)
+
+
+def test_workload_long64k_sampled():
+    _check_workload_sampled("long64k", n_per_type=3)
