@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparseD hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: full attention (emitting the row log-sum-exp), pattern selection (pooled scores +
+per-row top-k), and block-sparse attention with the selected pattern. The default workload is the
+64k long-context configuration the headline metric is quoted on. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload long64k] [--no-schedule] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_F32_TFLOPS = 157.3     # fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def _flops(cfg, keep):
+    dense = 4.0 * cfg.B * cfg.Hq * cfg.L * cfg.L * cfg.d
+    sparse = 4.0 * cfg.B * cfg.Hq * cfg.nqb * keep * cfg.bq * cfg.bk * cfg.d
+    select = 2.0 * cfg.B * cfg.Hq * cfg.L * cfg.L * cfg.d      # one algorithmic QK^T (statistics come from the dense call)
+    return dense, select, sparse
+
+
+def _traffic_from_profiles(workload_name):
+    """HBM bytes per launch of the sparse kernel from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"attn_sparse_{workload_name}_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    except Exception:
+        return None
+
+
+def cpu_baseline(cfg, q, k, v, index, keep, budget_s=20.0):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+
+    rng = np.random.default_rng(0)
+    group = cfg.Hq // cfg.Hkv
+    t_sparse = t_dense = 0.0
+    n_sparse = n_dense = 0
+    t0 = time.perf_counter()
+    heads = [int(h) for h in rng.permutation(cfg.Hq)[:4]]
+    for h in heads:
+        qh = q[:, h:h + 1].float().cpu()
+        kh = k[:, h // group:h // group + 1].float().cpu()
+        vh = v[:, h // group:h // group + 1].float().cpu()
+        rp = index.row_ptr[:, h:h + 1].cpu().numpy()
+        ci = index.col_idx[:, h:h + 1].cpu().numpy()
+        for I in [int(x) for x in rng.permutation(cfg.nqb)[:4]]:
+            if time.perf_counter() - t0 > budget_s:
+                break
+            a = time.perf_counter()
+            oracle.attn_sparse_rows(qh, kh, vh, rp, ci, cfg.bq, cfg.bk, 0, 0, I, I + 1)
+            t_sparse += time.perf_counter() - a
+            n_sparse += 1
+        if time.perf_counter() - t0 < budget_s:
+            I = int(rng.integers(cfg.nqb))
+            a = time.perf_counter()
+            oracle.attn_dense_rows(qh, kh, vh, 0, 0, I * cfg.bq, (I + 1) * cfg.bq)
+            t_dense += time.perf_counter() - a
+            n_dense += 1
+    unit_sparse = 4.0 * keep * cfg.bq * cfg.bk * cfg.d
+    unit_dense = 4.0 * cfg.bq * cfg.L * cfg.d
+    out = {
+        "value": (n_sparse * unit_sparse / t_sparse / 1e12) if t_sparse > 0 else None,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{n_sparse} (head, query-block) units of sparse attention and {n_dense} of dense attention "
+                  f"from the same {cfg.name} tensors, fp64, {t_sparse + t_dense:.1f} s of CPU work",
+        "dense_tflops": (n_dense * unit_dense / t_dense / 1e12) if t_dense > 0 else None,
+        "sparse_ms_full_tensor_extrapolated": (t_sparse / n_sparse * cfg.B * cfg.Hq * cfg.nqb * 1e3) if n_sparse else None,
+        "dense_ms_full_tensor_extrapolated": (t_dense / n_dense * cfg.B * cfg.Hq * cfg.nqb * 1e3) if n_dense else None,
+    }
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="long64k")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-schedule", action="store_true", help="skip the full T-step schedule run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards by head with no exchange; "
+              "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2509_24014_amd as sd
+    import workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sd.load_library(build_if_missing=True)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = workload.get_config(args.workload)
+    keep = sd.kept_blocks(cfg.rho, cfg.nkb)
+    inp = workload.make_inputs(cfg, seed=args.seed, device=dev)
+    q, k, v = inp.rounded()
+    out = torch.empty_like(q)
+    lse = torch.empty(cfg.B, cfg.Hq, cfg.L, dtype=torch.float32, device=dev)
+    ws = torch.empty(sd.select_workspace_bytes(q, cfg.bq, cfg.bk), dtype=torch.uint8, device=dev)
+    index = sd.BlockIndex(torch.empty(cfg.B, cfg.Hq, cfg.nqb + 1, dtype=torch.int32, device=dev),
+                          torch.empty(cfg.B, cfg.Hq, cfg.nqb * keep, dtype=torch.int32, device=dev), cfg.bq, cfg.bk, cfg.nkb)
+
+    def one_step(ev=None):
+        if ev:
+            ev[0].record()
+        sd.attn_dense(q, k, v, out=out, lse_out=lse)
+        if ev:
+            ev[1].record()
+        sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, lse_in=lse, workspace=ws, index=index)
+        if ev:
+            ev[2].record()
+        sd.attn_sparse(q, k, v, index, out=out)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(events[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dense_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    select_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    sparse_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+    ms_per_step = wall_ms / args.steps
+
+    f_dense, f_select, f_sparse = _flops(cfg, keep)
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12  # noqa: E731
+    sparse_tf, dense_tf, select_tf = tf(f_sparse, sparse_ms), tf(f_dense, dense_ms), tf(f_select, select_ms)
+
+    T, n_dense = cfg.T, cfg.n_dense
+    sched = None
+    if T > 1:
+        derived = (T * dense_ms) / (n_dense * dense_ms + select_ms + (T - n_dense) * sparse_ms)
+        expected = T / (n_dense + (T - n_dense) * keep / cfg.nkb + select_ms / dense_ms)
+        sched = {"T": T, "n_dense": n_dense, "speedup_from_call_times": derived, "expected_if_sparse_as_efficient_as_dense": expected}
+        if not args.no_schedule:
+            # the real thing: all T calls of Algorithm 1 with drifting inputs; only the attention calls are timed
+            layer = sd.SparseDLayer(T, 0.0, cfg.bq, cfg.bk, cfg.rho, n_dense=n_dense)
+            inp2 = workload.make_inputs(cfg, seed=args.seed, device=dev)
+            evs = []
+            for t in range(T):
+                qq, kk, vv = inp2.rounded()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                layer.step(qq, kk, vv, t, out=out)
+                b.record()
+                evs.append((a, b))
+                inp2.advance()
+                if t % 64 == 63:
+                    torch.cuda.synchronize()
+                    print(f"[bench] schedule step {t + 1}/{T}", file=sys.stderr, flush=True)
+            torch.cuda.synchronize()
+            total_ms = sum(a.elapsed_time(b) for a, b in evs)
+            sched.update({"total_attention_ms": total_ms, "dense_only_ms": T * dense_ms, "speedup_measured": T * dense_ms / total_ms,
+                          "calls": layer.calls})
+            del inp2
+
+    result = {
+        "metric": "ms/layer-call + executed TFLOP/s (% bf16 MFMA peak) for sparse attn at 64k; schedule speedup",
+        "value": sparse_tf,
+        "unit": "TFLOP/s (executed, sparse attention)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "L": cfg.L, "d": cfg.d,
+                   "block_q": cfg.bq, "block_k": cfg.bk, "rho": cfg.rho, "kept_blocks": keep, "step": "dense+select+sparse"},
+        "ms_per_call": {"dense": dense_ms, "select": select_ms, "sparse": sparse_ms},
+        "tflops": {"dense": dense_tf, "select_one_qkT": select_tf, "sparse_executed": sparse_tf,
+                   "sparse_dense_equivalent": tf(f_dense, sparse_ms)},
+        "pct_of_peak": {"dense": 100 * dense_tf / peak, "sparse_executed": 100 * sparse_tf / peak, "select_one_qkT": 100 * select_tf / peak},
+        "schedule": sched,
+        "roofline": {"kernel": "attn_sparse", "bound": "mfma", "achieved": sparse_tf, "peak": peak, "unit": "TFLOP/s",
+                     "frac": sparse_tf / peak, "traffic": _traffic_from_profiles(cfg.name)},
+        "roofline_dense": {"kernel": "attn_dense", "bound": "mfma", "achieved": dense_tf, "peak": peak, "unit": "TFLOP/s",
+                           "frac": dense_tf / peak},
+        "roofline_select": {"kernel": "select_pattern (pooled scores + top-k, statistics reused)", "bound": "mfma",
+                            "achieved": select_tf, "peak": peak, "unit": "TFLOP/s", "frac": select_tf / peak},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, index, keep)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
