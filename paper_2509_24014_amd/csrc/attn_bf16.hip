@@ -12,8 +12,10 @@
 
 namespace sparsed {
 
-template <int D, int NQ, int NW, Mode MODE>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a) {
+// EXACT_SUM: accumulate the softmax denominator from the unrounded fp32 probabilities. Used whenever
+// the row log-sum-exp is an output (pattern selection needs it to ~1e-7), at one more VALU op per key.
+template <int D, int NQ, int NW, Mode MODE, bool EXACT_SUM>
+__global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void attn_bf16_kernel(const AttnArgs a) {
   constexpr int NT = NW * 64;
   constexpr int QT = 32 * NQ * NW;
   constexpr bool kHasV = MODE != Mode::kStats;
@@ -95,6 +97,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a) {
   __syncthreads();
 
   const float c = a.scale_log2;
+  constexpr float kLazyLog2 = 8.0f;
   for (int t = 0; t < n_tiles; ++t) {
     const char* kl = lds + (t & 1) * (kKBytes + kVBytes);
     const char* vl = kl + kKBytes;
@@ -106,45 +109,69 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a) {
     bf16x8 pb[NQ][4];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      float mx = s[nq][0][0];
+      // row maximum of this tile (v_max3 chain over the lane's 32 keys, then the partner half)
+      float mx = fmaxf(s[nq][0][0], s[nq][0][1]);
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s[nq][ks][x]);
-      mx = fmaxf(mx, other_half(mx));
-      const float Mn = fmaxf(M[nq], mx * c);
-      const float alpha = __builtin_amdgcn_exp2f(M[nq] - Mn);
-      M[nq] = Mn;
-      float part = 0.f;
+        for (int x = (ks == 0 ? 2 : 0); x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][ks][x]), s[nq][ks][x + 1]);
+      mx = pair_max(mx);
+      // Lazy reference maximum: it is raised only when the tile maximum exceeds it by more than
+      // kLazyLog2 (probabilities then stay below 2^kLazyLog2, harmless in fp32 / bf16); the common
+      // case skips the rescale of the running sum and of the output accumulator altogether.
+      const float cand = mx * c;
+      const bool raise = cand > M[nq] + kLazyLog2;
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        const float Mn = raise ? cand : M[nq];
+        const float alpha = __builtin_amdgcn_exp2f(M[nq] - Mn);
+        M[nq] = Mn;
+        lsum[nq] *= alpha;
+        if (kHasV) {
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+          for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][x], c, -Mn));
-          s[nq][ks][x] = p;
-          part += p;
+            for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha;
         }
-      lsum[nq] = lsum[nq] * alpha + part;
-      if (kHasV) {
+      }
+      const float Mr = M[nq];
+      float part = 0.f;
+      if (kHasV && !EXACT_SUM) {
+        // p = 2^(s*c - M), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
+        // (v_dot2 with ones) so that numerator and denominator see the same probabilities.
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
           for (int m = 0; m < 2; ++m) {
-            bf16x8 pk;
+            u32x4 pk;
 #pragma unroll
             for (int x = 0; x < 8; x += 2) {
-              const f32x2 two = {s[nq][ks][8 * m + x], s[nq][ks][8 * m + x + 1]};
+              const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x], c, -Mr)),
+                                 __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x + 1], c, -Mr))};
               const bf16x2 r = __builtin_convertvector(two, bf16x2);
-              pk[x] = r[0];
-              pk[x + 1] = r[1];
+              part = __builtin_amdgcn_fdot2_f32_bf16(r, ones, part, false);
+              pk[x >> 1] = __builtin_bit_cast(uint32_t, r);
             }
-            pb[nq][2 * ks + m] = pk;
+            pb[nq][2 * ks + m] = __builtin_bit_cast(bf16x8, pk);
           }
+      } else {
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha;
+          for (int m = 0; m < 2; ++m) {
+            u32x4 pk;
+#pragma unroll
+            for (int x = 0; x < 8; x += 2) {
+              const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x], c, -Mr)),
+                                 __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x + 1], c, -Mr))};
+              part += two[0];
+              part += two[1];
+              if (kHasV) pk[x >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
+            }
+            if (kHasV) pb[nq][2 * ks + m] = __builtin_bit_cast(bf16x8, pk);
+          }
       }
+      lsum[nq] += part;
     }
 
     if (kHasV) {
@@ -166,7 +193,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a) {
   // epilogue: combine the two half-row sums, normalise, store
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    const float ltot = lsum[nq] + other_half(lsum[nq]);
+    const float ltot = pair_sum(lsum[nq]);
     const int row = row0 + nq * 32 + j;
     if (a.lse != nullptr && g == 0)
       a.lse[(int64_t)bh * a.L + row] = (M[nq] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
@@ -201,7 +228,11 @@ template <int D, int NQ, int NW, Mode MODE>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.n_qtiles;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE>), dim3((unsigned)total), dim3(NW * 64), 0, s, a);
+  const dim3 grid((unsigned)total), block(NW * 64);
+  if (MODE == Mode::kStats || (MODE == Mode::kDense && a.lse != nullptr))
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, true>), grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, false>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 

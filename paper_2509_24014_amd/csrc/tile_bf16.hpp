@@ -28,8 +28,19 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kTileK = 64;  // keys per K/V tile of the bf16 kernels (= block_k)
 
-// Value held by the partner lane (lane ^ 32).
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// Lanes j and j+32 hold the two halves of one query's keys. v_permlane32_swap exchanges the upper
+// 32 lanes of its first operand with the lower 32 lanes of its second; fed the same value twice it
+// returns {x[lane % 32], x[32 + lane % 32]} in every lane, i.e. both halves of the pair.
+__device__ __forceinline__ float pair_max(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
