@@ -3,8 +3,17 @@
 //
 // One work-group owns QT = 32*NQ*NW query rows of one (batch, head) and walks 64-key tiles:
 // all of them (dense, stats) or the key blocks listed for its query block (sparse; QT == block_q,
-// so all rows of the group share one list). K and V tiles are staged global -> registers -> LDS,
-// double-buffered, one barrier per tile; V is transposed on the way in (tile_bf16.hpp).
+// so all rows of the group share one list). K and V tiles are copied global -> LDS directly,
+// double-buffered, one barrier per tile (tile_bf16.hpp).
+//
+// Software pipeline inside every wave. On this chip a matrix instruction runs in the background
+// of the wave that issued it while that same wave keeps issuing vector instructions, but matrix
+// work of one wave and vector work of ANOTHER wave on the same SIMD get in each other's way. So
+// a wave works in sub-steps of 32 keys, and sub-step u interleaves, in one instruction stream,
+//      matrix:  O += P(u-1) V(u-1)   and   S(u+1) = K(u+1) Q^T
+//      vector:  online softmax of S(u)  ->  P(u), running max / sum
+// which are independent of each other; S and P are double-buffered in registers (even / odd
+// sub-steps) and the tile loop is unrolled by two so that the LDS buffer roles are static.
 // Softmax is online (running max / running sum per query, fp32); probabilities are rounded to
 // bf16 for the second matrix product; the output accumulator is fp32.
 #include "kernels.hpp"
@@ -15,15 +24,23 @@ namespace sparsed {
 // EXACT_SUM: accumulate the softmax denominator from the unrounded fp32 probabilities. Used whenever
 // the row log-sum-exp is an output (pattern selection needs it to ~1e-7), at one more VALU op per key.
 template <int D, int NQ, int NW, Mode MODE, bool EXACT_SUM>
-__global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void attn_bf16_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(NW * 64)
+    __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? 2 : 1, (NQ == 1 && NW >= 4) ? 2 : 1))) void attn_bf16_kernel(const AttnArgs a) {
   constexpr int NT = NW * 64;
   constexpr int QT = 32 * NQ * NW;
   constexpr bool kHasV = MODE != Mode::kStats;
-  constexpr int kKBytes = kTileK * D * 2;
-  constexpr int kVBytes = kHasV ? D * kTileK * 2 : 0;
-  __shared__ __attribute__((aligned(16))) char lds[2 * (kKBytes + kVBytes)];
+  constexpr int kKBytes = KLayout<D>::kTileBytes;
+  constexpr int kVBytes = kHasV ? VLayout<D>::kTileBytes : 16;
+  constexpr float kLazyLog2 = 8.0f;
+  // Four separate LDS objects on purpose: the compiler tells accesses to different LDS variables
+  // apart, so a copy in flight into one buffer does not hold up fragment reads from the others.
+  __shared__ __attribute__((aligned(1024))) char kbuf0[kKBytes];
+  __shared__ __attribute__((aligned(1024))) char kbuf1[kKBytes];
+  __shared__ __attribute__((aligned(1024))) char vbuf0[kVBytes];
+  __shared__ __attribute__((aligned(1024))) char vbuf1[kVBytes];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
   const int j = lane & 31, g = lane >> 5;
 
   const int lid = xcd_remap(blockIdx.x, gridDim.x);
@@ -38,15 +55,15 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void attn_bf16_kernel(c
   const int row0 = qt * QT + wave * (32 * NQ);  // first query row of this wave
 
   // key tiles to visit
-  int n_tiles;
+  int n;
   const int32_t* cols = nullptr;
   if (MODE == Mode::kSparse) {
     const int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1) + qt;
     const int beg = rp[0], end = rp[1];
-    n_tiles = end - beg;
+    n = end - beg;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
-    n_tiles = a.L / kTileK;
+    n = a.L / kTileK;
   }
 
   QFrag<D, NQ> qf;
@@ -63,134 +80,165 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void attn_bf16_kernel(c
 #pragma unroll
       for (int x = 0; x < 16; ++x) o[nq][dt][x] = 0.f;
   }
+  f32x16 s_even[NQ], s_odd[NQ];        // logits of the even / odd 32-key sub-tiles in flight
+  bf16x8 p_even[NQ][2], p_odd[NQ][2];  // their probabilities
 
-  // Staging roles. With 8 waves the upper four stage K and the lower four stage V; otherwise
-  // every thread stages its share of both (V units may be fewer than threads).
-  constexpr int NTK = (NT == 512) ? 256 : NT;
-  constexpr int kVUnits = (kTileK / 4) * (D / 8);
-  constexpr int NTV = (NT == 512) ? 256 : (NT < kVUnits ? NT : kVUnits);
-  constexpr int NTV2 = NTV < kVUnits ? NTV : kVUnits;
-  const int ktid = (NT == 512 && kHasV) ? tid - 256 : tid;
-  const bool k_role = (NT == 512 && kHasV) ? (tid >= 256) : (tid < NTK);
-  const bool v_role = kHasV && tid < NTV2;
-  KStage<D, NTK> kst;
-  VStage<D, NTV2> vst;
-  auto tile_key0 = [&](int t) -> int {
-    const int blk = (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(cols[t]) : t;
-    return blk * kTileK;
-  };
-  auto issue = [&](int t) {
-    const int key0 = tile_key0(t);
-    if (k_role) kst.load(kbase + (int64_t)key0 * a.k.sl, a.k.sl, ktid);
-    if (v_role) vst.load(vbase + (int64_t)key0 * a.v.sl, a.v.sl, tid);
-  };
-  auto commit = [&](int buf) {
-    char* base = lds + buf * (kKBytes + kVBytes);
-    if (k_role) kst.store(base, ktid);
-    if (v_role) vst.store(base + kKBytes, tid);
-  };
+  TileDma<D, NT, false> kdma;
+  TileDma<D, NT, true> vdma;
+  kdma.init(a.k.sl, wave, lane);
+  if (kHasV) vdma.init(a.v.sl, wave, lane);
+  KFragAddr<D> kaddr;
+  VFragAddr<D> vaddr;
+  kaddr.init(lane);
+  vaddr.init(lane);
 
-  if (n_tiles > 0) {
-    issue(0);
-    commit(0);
-  }
-  __syncthreads();
+  // Sliding window of key-block numbers: blk_i is the block of tile t+i. For sparse the list is
+  // read four tiles ahead of its first use, with a VECTOR load on purpose (an opaque zero keeps the
+  // address off the scalar path): scalar loads share a counter with LDS reads and return out of
+  // order, which would force every fragment read issued meanwhile to be waited for in full.
+  int opaque_zero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
+  auto col_at = [&](int t) -> int {
+    if (MODE != Mode::kSparse) return t;
+    const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
+    return cols[idx + opaque_zero];
+  };
+  int blk0 = col_at(0), blk1 = col_at(1), blk2 = col_at(2), blk3 = col_at(3);
+  auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
+  auto copy_k = [&](int blk, char* dst) { kdma.issue(kbase + (int64_t)uni(blk) * kTileK * a.k.sl, dst, wave); };
+  auto copy_v = [&](int blk, char* dst) { vdma.issue(vbase + (int64_t)uni(blk) * kTileK * a.v.sl, dst, wave); };
 
   const float c = a.scale_log2;
-  constexpr float kLazyLog2 = 8.0f;
-  for (int t = 0; t < n_tiles; ++t) {
-    const char* kl = lds + (t & 1) * (kKBytes + kVBytes);
-    const char* vl = kl + kKBytes;
-    if (t + 1 < n_tiles) issue(t + 1);
 
-    f32x16 s[NQ][2];
-    logits_tile<D, NQ>(kl, qf, lane, s);
-
-    bf16x8 pb[NQ][4];
+  // Online softmax of one 32-key sub-tile: s (fp32 logits) -> p (bf16), updates M / lsum, reports the
+  // factor by which the output accumulator has to be rescaled (1 unless the reference maximum moved).
+  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise) {
+    any_raise = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      // row maximum of this tile (v_max3 chain over the lane's 32 keys, then the partner half)
-      float mx = fmaxf(s[nq][0][0], s[nq][0][1]);
+      float mx = fmaxf(s[nq][0], s[nq][1]);
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int x = (ks == 0 ? 2 : 0); x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][ks][x]), s[nq][ks][x + 1]);
+      for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][x]), s[nq][x + 1]);
       mx = pair_max(mx);
-      // Lazy reference maximum: it is raised only when the tile maximum exceeds it by more than
-      // kLazyLog2 (probabilities then stay below 2^kLazyLog2, harmless in fp32 / bf16); the common
-      // case skips the rescale of the running sum and of the output accumulator altogether.
+      // Lazy reference maximum: raised only when the sub-tile maximum exceeds it by more than
+      // kLazyLog2 (probabilities then stay below 2^kLazyLog2, harmless in fp32 / bf16).
       const float cand = mx * c;
       const bool raise = cand > M[nq] + kLazyLog2;
-      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-        const float Mn = raise ? cand : M[nq];
-        const float alpha = __builtin_amdgcn_exp2f(M[nq] - Mn);
-        M[nq] = Mn;
-        lsum[nq] *= alpha;
+      const float Mn = raise ? cand : M[nq];
+      alpha[nq] = raise ? __builtin_amdgcn_exp2f(M[nq] - Mn) : 1.0f;
+      any_raise = any_raise || (__builtin_amdgcn_ballot_w64(raise) != 0);
+      M[nq] = Mn;
+      float part = 0.f;
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        u32x4 pk;
+#pragma unroll
+        for (int x = 0; x < 8; x += 2) {
+          const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x], c, -Mn)),
+                             __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x + 1], c, -Mn))};
+          if (kHasV) {
+            const bf16x2 r = __builtin_convertvector(two, bf16x2);
+            pk[x >> 1] = __builtin_bit_cast(uint32_t, r);
+            // row sum over the ROUNDED values: numerator and denominator see the same probabilities
+            if (!EXACT_SUM) part = __builtin_amdgcn_fdot2_f32_bf16(r, ones, part, false);
+          }
+          if (EXACT_SUM || !kHasV) {
+            part += two[0];
+            part += two[1];
+          }
+        }
         if (kHasV) {
-#pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha;
+          // pin: the probabilities must exist HERE, inside the block that holds the matrix
+          // instructions, not be sunk by the compiler past the (rare) rescale branch that follows
+          asm volatile("" : "+v"(pk));
+          p[nq][m] = __builtin_bit_cast(bf16x8, pk);
         }
       }
-      const float Mr = M[nq];
-      float part = 0.f;
-      if (kHasV && !EXACT_SUM) {
-        // p = 2^(s*c - M), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
-        // (v_dot2 with ones) so that numerator and denominator see the same probabilities.
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int m = 0; m < 2; ++m) {
-            u32x4 pk;
-#pragma unroll
-            for (int x = 0; x < 8; x += 2) {
-              const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x], c, -Mr)),
-                                 __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x + 1], c, -Mr))};
-              const bf16x2 r = __builtin_convertvector(two, bf16x2);
-              part = __builtin_amdgcn_fdot2_f32_bf16(r, ones, part, false);
-              pk[x >> 1] = __builtin_bit_cast(uint32_t, r);
-            }
-            pb[nq][2 * ks + m] = __builtin_bit_cast(bf16x8, pk);
-          }
-      } else {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int m = 0; m < 2; ++m) {
-            u32x4 pk;
-#pragma unroll
-            for (int x = 0; x < 8; x += 2) {
-              const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x], c, -Mr)),
-                                 __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][ks][8 * m + x + 1], c, -Mr))};
-              part += two[0];
-              part += two[1];
-              if (kHasV) pk[x >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
-            }
-            if (kHasV) pb[nq][2 * ks + m] = __builtin_bit_cast(bf16x8, pk);
-          }
-      }
-      lsum[nq] += part;
+      lsum[nq] = lsum[nq] * alpha[nq] + part;
+      asm volatile("" : "+v"(lsum[nq]));
     }
-
-    if (kHasV) {
+  };
+  auto rescale_output = [&](const float(&alpha)[NQ]) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int mp = 0; mp < 4; ++mp) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vl + vt_lds_offset(32 * dt + j, 2 * mp + g));
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq)
-            o[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[nq][mp], o[nq][dt], 0, 0, 0);
-        }
-    }
+        for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha[nq];
+  };
 
-    if (t + 1 < n_tiles) commit((t + 1) & 1);
-    __syncthreads();
+  // Tile step t (LDS parity P = t & 1) = sub-steps 2t+1 and 2t+2 of the 32-key pipeline.
+  // On entry: S(2t+1) in s_odd, P(2t) in p_even, K(t+1) in kbuf[1-P], V(t) in vbuf[P]; the buffers
+  // kbuf[P] (held K(t)) and vbuf[1-P] (held V(t-1)) are free and receive K(t+2) and V(t+1).
+  //   sub-step 2t+1:  S(2t+2) = K(t+1)[0:32] Q^T,   O += P(2t)   V(t)[0:32],   softmax(2t+1) -> p_odd
+  //   sub-step 2t+2:  S(2t+3) = K(t+1)[32:64] Q^T,  O += P(2t+1) V(t)[32:64],  softmax(2t+2) -> p_even
+  // STEADY: t + 2 < n, every piece exists and each sub-step is one branch-free block.
+#define SPARSED_TILE_STEP(P, STEADY, T)                                                            \
+  {                                                                                                \
+    char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
+    char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
+    char* const vb_this = (P) ? vbuf1 : vbuf0;                                                     \
+    char* const vb_free = (P) ? vbuf0 : vbuf1;                                                     \
+    const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
+    const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
+    if (has_k2) copy_k(blk2, kb_free);                                                             \
+    if (kHasV && has_next) copy_v(blk1, vb_free);                                                  \
+    const int blk_new = col_at((T) + 4);                                                           \
+    float alpha[NQ];                                                                               \
+    bool any_raise;                                                                                \
+    if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                     \
+    if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 0, vaddr, p_even, o);                             \
+    softmax_sub(s_odd, p_odd, alpha, any_raise);                                                   \
+    if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                          \
+    if (kHasV && any_raise) rescale_output(alpha);                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                             \
+    if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                      \
+    if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 1, vaddr, p_odd, o);                              \
+    if (has_next) {                                                                                \
+      softmax_sub(s_even, p_even, alpha, any_raise);                                               \
+      if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                        \
+      if (kHasV && any_raise) rescale_output(alpha);                                               \
+    }                                                                                              \
+    blk0 = blk1;                                                                                   \
+    blk1 = blk2;                                                                                   \
+    blk2 = blk3;                                                                                   \
+    blk3 = blk_new;                                                                                \
+    __syncthreads();                                                                               \
   }
 
-  // epilogue: combine the two half-row sums, normalise, store
+  if (n > 0) {
+    // prologue: K(0), K(1), V(0) into LDS; S(0); then sub-step 0: S(1) alongside softmax(0)
+    copy_k(blk0, kbuf0);
+    if (n > 1) copy_k(blk1, kbuf1);
+    if (kHasV) copy_v(blk0, vbuf0);
+    __syncthreads();
+    logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
+    logits_sub<D, NQ, true>(kbuf0, 1, kaddr, qf, s_odd);
+    {
+      float alpha[NQ];
+      bool any_raise;
+      softmax_sub(s_even, p_even, alpha, any_raise);  // O is still zero: nothing to rescale
+    }
+    __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
+
+    int t = 0;
+    while (t + 3 < n) {
+      SPARSED_TILE_STEP(0, true, t);
+      SPARSED_TILE_STEP(1, true, t + 1);
+      t += 2;
+    }
+    for (; t < n; ++t) {
+      if (t & 1) {
+        SPARSED_TILE_STEP(1, false, t);
+      } else {
+        SPARSED_TILE_STEP(0, false, t);
+      }
+    }
+  }
+#undef SPARSED_TILE_STEP
+
+  // combine the two half-row sums, normalise, store
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const float ltot = pair_sum(lsum[nq]);
@@ -206,11 +254,9 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void attn_bf16_kernel(c
         for (int q4 = 0; q4 < 4; ++q4) {
           const f32x2 lo = {o[nq][dt][4 * q4] * inv, o[nq][dt][4 * q4 + 1] * inv};
           const f32x2 hi = {o[nq][dt][4 * q4 + 2] * inv, o[nq][dt][4 * q4 + 3] * inv};
-          const bf16x2 l2 = __builtin_convertvector(lo, bf16x2);
-          const bf16x2 h2 = __builtin_convertvector(hi, bf16x2);
           u32x2 w;
-          w[0] = *reinterpret_cast<const uint32_t*>(&l2);
-          w[1] = *reinterpret_cast<const uint32_t*>(&h2);
+          w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+          w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
           *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q4 + 4 * g) = w;
         }
     }
@@ -229,10 +275,16 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.n_qtiles;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)total), block(NW * 64);
-  if (MODE == Mode::kStats || (MODE == Mode::kDense && a.lse != nullptr))
+  if constexpr (MODE == Mode::kStats) {
     hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, true>), grid, block, 0, s, a);
-  else
+  } else if constexpr (MODE == Mode::kDense) {
+    if (a.lse != nullptr)
+      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, true>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, false>), grid, block, 0, s, a);
+  } else {
     hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, false>), grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -15,9 +15,9 @@ namespace sparsed {
 
 // ---------------------------------------------------------------------------- pooled scores, bf16
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void pool_bf16_kernel(const PoolArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void pool_bf16_kernel(const PoolArgs a) {
   constexpr int NT = NW * 64;
-  constexpr int kKBytes = kTileK * D * 2;
+  constexpr int kKBytes = KLayout<D>::kTileBytes;
   __shared__ __attribute__((aligned(16))) char lds[2 * kKBytes];
   __shared__ float wsum[2][NW];
 
@@ -38,28 +38,30 @@ __global__ __launch_bounds__(NW * 64) void pool_bf16_kernel(const PoolArgs a) {
   const float lse2 = a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f;
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.nkb;
 
-  KStage<D, NT> kst;
+  TileDma<D, NT, false> kdma;
+  kdma.init(a.k.sl, wave, lane);
+  KFragAddr<D> kaddr;
+  kaddr.init(lane);
   const int n_tiles = a.nkb;
-  kst.load(kbase, a.k.sl, tid);
-  kst.store(lds, tid);
+  kdma.issue(kbase, lds, wave);
   __syncthreads();
 
   const float c = a.scale_log2;
   for (int t = 0; t < n_tiles; ++t) {
     const char* kl = lds + (t & 1) * kKBytes;
-    if (t + 1 < n_tiles) kst.load(kbase + (int64_t)(t + 1) * kTileK * a.k.sl, a.k.sl, tid);
+    if (t + 1 < n_tiles) kdma.issue(kbase + (int64_t)(t + 1) * kTileK * a.k.sl, lds + ((t + 1) & 1) * kKBytes, wave);
 
-    f32x16 s[1][2];
-    logits_tile<D, 1>(kl, qf, lane, s);
+    f32x16 s0[1], s1[1];
+    logits_sub<D, 1, true>(kl, 0, kaddr, qf, s0);
+    logits_sub<D, 1, true>(kl, 1, kaddr, qf, s1);
     float part = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s0[0][x], c, -lse2));
 #pragma unroll
-      for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][ks][x], c, -lse2));
+    for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s1[0][x], c, -lse2));
     part = wave_sum(part);
     if (lane == 0) wsum[t & 1][wave] = part;
 
-    if (t + 1 < n_tiles) kst.store(lds + ((t + 1) & 1) * kKBytes, tid);
     __syncthreads();
     if (tid == 0) {
       float tot = 0.f;

@@ -11,8 +11,15 @@
 // lane (j, g) ends up holding, in registers 8m .. 8m+7 of the accumulator, the 8 CONSECUTIVE keys
 // 16m + 8g .. 16m + 8g + 7 of the 32-key sub-tile. Those 8 probabilities, rounded to bf16, are
 // exactly the B operand of the second product  O^T[d, query] += V^T[d, key] . P^T[key, query],
-// whose A operand is 8 consecutive keys of one column d of V: one 16-byte read from a K-major
-// (transposed) copy of the V tile in LDS. The output accumulator again has one query per lane.
+// whose A operand is 8 consecutive keys of one column d of V. The output accumulator again has
+// one query per lane.
+//
+// Data path. K and V tiles go global -> LDS directly (global_load_lds_dwordx4: lane i of a wave
+// deposits its 16 bytes at LDS base + 16*i); the LDS layouts below are realised on the GLOBAL side
+// (each lane fetches the chunk that belongs in its LDS slot). K fragments are 16-byte LDS reads. V fragments use the LDS
+// transpose read ds_read_b64_tr_b16: within a block of 16 lanes, result lane L gets element (L%4)
+// of the 8 bytes addressed by lanes L/4, 4 + L/4, 8 + L/4, 12 + L/4; addressing lane s to
+// V[key0 + s/4][col0 + 4*(s%4) ..] hands lane L the four keys key0 .. key0+3 of column col0 + L.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,8 +32,12 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kTileK = 64;  // keys per K/V tile of the bf16 kernels (= block_k)
+
+#define SPARSED_LDS __attribute__((address_space(3)))
+#define SPARSED_GLOBAL __attribute__((address_space(1)))
 
 // Lanes j and j+32 hold the two halves of one query's keys. v_permlane32_swap exchanges the upper
 // 32 lanes of its first operand with the lower 32 lanes of its second; fed the same value twice it
@@ -57,96 +68,81 @@ __device__ __forceinline__ int xcd_remap(int wg, int total) {
   return x * q + (x < r ? x : r) + n;
 }
 
-// ---- K tile in LDS: [64 keys][D] bf16, 16-byte chunks XOR-swizzled per row --------------------
-// Row r keeps chunk c at position c ^ kswz(r). kswz is distinct over the 8 rows an aligned group
-// of 8 lanes reads (rows {0..3, 8..11} or {4..7, 12..15} after the row permutation).
-__device__ __forceinline__ int kswz(int r) { return (r & 3) | ((r >> 1) & 4); }
+// ---- LDS layouts ---------------------------------------------------------------------------------
+// LDS serves 256 bytes (64 banks) per clock: a 16-byte-per-lane read is conflict-free when every
+// group of 16 consecutive lanes touches 16 different 16-byte positions modulo 256, an 8-byte
+// transpose read when every 32 lanes do. A direct global->LDS load writes one contiguous KB per
+// wave, so layouts are built from 1 KB pieces; inside a piece the order of the 64 chunks is free
+// (each lane simply fetches the chunk that belongs in its slot).
+//
+// K tile, D = 128 (one KB = 4 rows): the 16 lanes of a fragment read take the SAME logical chunk
+// of 16 consecutive rows. Row r keeps chunk c at position c ^ (r & 3) and every 4-row piece is
+// padded by 64 bytes, which shifts piece q by 4*q positions: 16 rows -> 16 distinct positions.
+// K tile, D = 64 (one KB = 8 rows of 128 bytes): row r keeps chunk c at c ^ ((r >> 1) & 7).
+template <int D>
+struct KLayout {
+  static constexpr int kPieceBytes = (D == 128) ? 1024 + 64 : 1024;
+  static constexpr int kRowsPerPiece = 1024 / (2 * D);
+  static constexpr int kTileBytes = (kTileK / kRowsPerPiece) * kPieceBytes;
+  __device__ static __forceinline__ int swz(int r) { return (D == 128) ? (r & 3) : ((r >> 1) & 7); }
+  __device__ static __forceinline__ int offset(int r, int c) {  // bytes, logical chunk c of row r
+    return (r / kRowsPerPiece) * kPieceBytes + (r % kRowsPerPiece) * (2 * D) + ((c ^ swz(r)) << 4);
+  }
+};
+// V tile (one piece = 4 rows = 8*D bytes): a transpose read by 32 lanes takes 4 consecutive rows x
+// 4 consecutive chunks (one 32-column slice dt). Piece layout [dt][row & 3][chunk & 3]: those 16
+// chunks are 256 contiguous bytes.
+template <int D>
+struct VLayout {
+  static constexpr int kPieceBytes = 8 * D;
+  static constexpr int kTileBytes = kTileK * 2 * D;
+  __device__ static __forceinline__ int offset(int r, int c) {
+    return (r >> 2) * kPieceBytes + ((c >> 2) << 8) + ((r & 3) << 6) + ((c & 3) << 4);
+  }
+};
 // Permutation of the K rows fed to the first product: swap bits 2 and 3.
 __device__ __forceinline__ int krow_perm(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
-template <int D>
-__device__ __forceinline__ int k_lds_offset(int row, int chunk) {  // bytes
-  return row * (2 * D) + ((chunk ^ kswz(row)) << 4);
-}
+// Direct global -> LDS copy of one [64][D] bf16 tile by NT threads (NT/64 waves). Per-lane byte
+// offsets into the global tile are precomputed once (they depend on the row stride and the lane
+// only); per tile a wave issues kPerWave 16-byte-per-lane loads, each filling one KB of LDS.
+template <int D, int NT, bool IS_V>
+struct TileDma {
+  static constexpr int kWaveLoads = kTileK * D * 2 / 1024;
+  static constexpr int kWaves = NT / 64;
+  static constexpr int kPerWave = kWaveLoads / kWaves;
+  static_assert(kWaveLoads % kWaves == 0, "tile must split evenly over the waves");
+  int32_t goff[kPerWave];  // byte offset of this lane's chunk within the global tile, per wave-load
 
-// ---- V tile in LDS, transposed: [D][64 keys] bf16 (128 bytes per row) -------------------------
-// Row d keeps the 16-byte chunk c (keys 8c .. 8c+7) at position c ^ vswz(d).
-__device__ __forceinline__ int vswz(int d) { return ((d >> 3) ^ d) & 7; }
-__device__ __forceinline__ int vt_lds_offset(int d, int chunk) {  // bytes
-  return d * (2 * kTileK) + ((chunk ^ vswz(d)) << 4);
-}
-
-// Cooperative global -> register -> LDS staging of one K tile by NT threads.
-template <int D, int NT>
-struct KStage {
-  static constexpr int kChunks = kTileK * D / 8;  // 16-byte chunks in the tile
-  static constexpr int kPer = kChunks / NT;
-  static_assert(kChunks % NT == 0, "K tile must split evenly");
-  u32x4 r[kPer];
-
-  __device__ __forceinline__ void load(const __bf16* tile, int64_t stride_l, int tid) {
-#pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-      const int id = c * NT + tid;
-      const int row = id / (D / 8), ch = id % (D / 8);
-      r[c] = *reinterpret_cast<const u32x4*>(tile + (int64_t)row * stride_l + ch * 8);
-    }
+  __device__ static __forceinline__ int lds_piece_offset(int wl) {  // where KB number wl of the tile goes
+    if (IS_V) return wl * 1024;
+    return wl * KLayout<D>::kPieceBytes;
   }
-  __device__ __forceinline__ void store(char* lds, int tid) const {
+  __device__ __forceinline__ void init(int64_t stride_l, int wave_in_group, int lane) {
 #pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-      const int id = c * NT + tid;
-      const int row = id / (D / 8), ch = id % (D / 8);
-      *reinterpret_cast<u32x4*>(lds + k_lds_offset<D>(row, ch)) = r[c];
-    }
-  }
-};
-
-// Cooperative staging of one V tile, transposed on the way into LDS. A unit is 4 consecutive keys
-// x 8 consecutive columns: four 16-byte global loads, then for each of the 8 columns the four keys'
-// values are packed (v_perm_b32) into one 8-byte LDS write. The unit -> thread map makes every
-// aligned group of 8 lanes read one full 128-byte line and every aligned group of 16 lanes write
-// 16 distinct 8-byte LDS slots.
-template <int D, int NT>
-struct VStage {
-  static constexpr int kUnits = (kTileK / 4) * (D / 8);
-  static constexpr int kPer = kUnits / NT;
-  static_assert(kUnits % NT == 0, "V tile must split evenly");
-  u32x4 r[kPer][4];
-
-  __device__ static __forceinline__ void decode(int u, int& kq, int& dc) {
-    if (D == 128) {
-      dc = (u & 7) | ((u >> 1) & 8);
-      kq = ((u >> 3) & 1) | ((u >> 4) & 14);
-    } else {
-      dc = u & 7;
-      kq = (u >> 3) & 15;
-    }
-  }
-  __device__ __forceinline__ void load(const __bf16* tile, int64_t stride_l, int tid) {
-#pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-      int kq, dc;
-      decode(c * NT + tid, kq, dc);
-#pragma unroll
-      for (int x = 0; x < 4; ++x)
-        r[c][x] = *reinterpret_cast<const u32x4*>(tile + (int64_t)(4 * kq + x) * stride_l + dc * 8);
-    }
-  }
-  __device__ __forceinline__ void store(char* lds, int tid) const {
-#pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-      int kq, dc;
-      decode(c * NT + tid, kq, dc);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 w;
-        w[0] = __builtin_amdgcn_perm(r[c][1][e >> 1], r[c][0][e >> 1], sel);
-        w[1] = __builtin_amdgcn_perm(r[c][3][e >> 1], r[c][2][e >> 1], sel);
-        const int d = dc * 8 + e;
-        *reinterpret_cast<u32x2*>(lds + vt_lds_offset(d, kq >> 1) + ((kq & 1) << 3)) = w;
+    for (int u = 0; u < kPerWave; ++u) {
+      const int wl = wave_in_group * kPerWave + u;
+      int row, chunk;
+      if (IS_V) {
+        const int slot = wl * 64 + lane;             // 16-byte slot within the tile
+        const int piece = slot / (D / 2), sp = slot % (D / 2);
+        row = 4 * piece + ((sp >> 2) & 3);
+        chunk = 4 * (sp >> 4) + (sp & 3);
+      } else {
+        const int rpp = KLayout<D>::kRowsPerPiece, cpr = D / 8;
+        row = wl * rpp + lane / cpr;
+        chunk = (lane % cpr) ^ KLayout<D>::swz(row);
       }
+      goff[u] = (int32_t)(row * stride_l * 2 + chunk * 16);
+    }
+  }
+  // tile: global address of the tile's first row (wave-uniform); lds_tile: LDS address of the tile.
+  __device__ __forceinline__ void issue(const __bf16* tile, char* lds_tile, int wave_in_group) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const char* src = reinterpret_cast<const char*>(tile) + goff[u];
+      char* dst = lds_tile + lds_piece_offset(wave_in_group * kPerWave + u);
+      __builtin_amdgcn_global_load_lds((const SPARSED_GLOBAL void*)src, (SPARSED_LDS void*)dst, 16, 0, 0);
     }
   }
 };
@@ -166,25 +162,117 @@ struct QFrag {
   }
 };
 
-// S^T for one 64-key tile: s[nq][ks] (ks = 32-key sub-tile) = K_sub . Q_nq^T, fp32.
-template <int D, int NQ>
-__device__ __forceinline__ void logits_tile(const char* klds, const QFrag<D, NQ>& q, int lane,
-                                            f32x16 (&s)[NQ][2]) {
-  const int i = lane & 31, g = lane >> 5;
-  const int prow = krow_perm(i);
+// Per-lane LDS addressing of the K fragments. Lane (i, g) reads, for sub-tile ks and k-step kk, the
+// logical chunk 2*kk + g of row 32*ks + perm(i). The swizzle flips bit 0 (g) and the low bits of kk
+// by a lane-dependent mask: a handful of per-lane bases, everything else is an immediate.
+template <int D>
+struct KFragAddr {
+  static constexpr int kBases = (D == 128) ? 2 : 4;
+  int32_t base[kBases];
+  __device__ __forceinline__ void init(int lane) {
+    const int i = lane & 31, g = lane >> 5;
+    const int prow = krow_perm(i);
+    const int y = KLayout<D>::swz(prow);
+    const int row_part = KLayout<D>::offset(prow, 0) - ((0 ^ y) << 4);
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
+    for (int bq = 0; bq < kBases; ++bq) base[bq] = row_part + 16 * (g ^ (y & 1)) + 32 * (bq ^ (y >> 1));
+  }
+  __device__ __forceinline__ bf16x8 read(const char* ktile, int ks, int kk) const {
+    const int sub = ks * (32 / KLayout<D>::kRowsPerPiece) * KLayout<D>::kPieceBytes;
+    return *reinterpret_cast<const bf16x8*>(ktile + base[kk % kBases] + (kk / kBases) * kBases * 32 + sub);
+  }
+};
+
+// Per-lane LDS addressing of the V fragments (transpose reads). For column slice dt, 16-key step mp
+// and half rr, lane l = 32g + 16*blk + Lb addresses row 16*mp + 8*g + 4*rr + Lb/4, logical chunk
+// 4*dt + 2*blk + (Lb&3)/2, byte 8*(Lb&1) within the chunk: one per-lane base plus immediates.
+template <int D>
+struct VFragAddr {
+  int32_t base;
+  __device__ __forceinline__ void init(int lane) {
+    const int g = lane >> 5, blk = (lane >> 4) & 1, Lb = lane & 15;
+    base = VLayout<D>::offset(8 * g + (Lb >> 2), 2 * blk + ((Lb & 3) >> 1)) + 8 * (Lb & 1);
+  }
+  // 8 consecutive keys 16*mp + 8*g .. +7 of column 32*dt + (lane % 32)
+  __device__ __forceinline__ bf16x8 read(const char* vtile, int dt, int mp) const {
+    const int32_t b = base + 4 * mp * VLayout<D>::kPieceBytes + 256 * dt;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SPARSED_LDS s16x4*)(vtile + b));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SPARSED_LDS s16x4*)(vtile + b + VLayout<D>::kPieceBytes));
+    u32x4 w;
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    w[0] = l2[0];
+    w[1] = l2[1];
+    w[2] = h2[0];
+    w[3] = h2[1];
+    return __builtin_bit_cast(bf16x8, w);
+  }
+};
+
+// Scheduling hints: ask the backend to lay the enclosing block out as `AHEAD` fragments' worth of
+// LDS reads, then (one fragment's matrix ops, one fragment's reads) repeated, then the remaining
+// matrix ops. Without this the compiler issues every fragment read right before the MFMA that
+// consumes it and eats the full LDS latency once per fragment.
+template <int N_FRAGS, int READS_PER_FRAG, int MFMA_PER_FRAG, int AHEAD>
+__device__ __forceinline__ void sched_reads_ahead_of_mfma() {
+  __builtin_amdgcn_sched_group_barrier(0x100, AHEAD * READS_PER_FRAG, 0);
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
+  for (int i = 0; i < N_FRAGS - AHEAD; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_FRAG, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, READS_PER_FRAG, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, AHEAD * MFMA_PER_FRAG, 0);
+}
+
+// S^T for one 32-key sub-tile (ks = 0 / 1 of a 64-key tile): s[nq] = K_sub . Q_nq^T, fp32.
+template <int D, int NQ, bool HINT>
+__device__ __forceinline__ void logits_sub(const char* klds, int ks, const KFragAddr<D>& ka, const QFrag<D, NQ>& q,
+                                           f32x16 (&s)[NQ]) {
 #pragma unroll
-      for (int x = 0; x < 16; ++x) s[nq][ks][x] = 0.f;
+  for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(klds + k_lds_offset<D>(32 * ks + prow, 2 * kk + g));
+    for (int x = 0; x < 16; ++x) s[nq][x] = 0.f;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
-        s[nq][ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q.f[nq][kk], s[nq][ks], 0, 0, 0);
+  for (int kk = 0; kk < D / 16; ++kk) {
+    const bf16x8 kf = ka.read(klds, ks, kk);
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) s[nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q.f[nq][kk], s[nq], 0, 0, 0);
+  }
+  if (HINT) sched_reads_ahead_of_mfma<D / 16, 1, NQ, 4>();
+}
+
+// O^T += V^T . P^T for one 32-key sub-tile: p[nq][m] holds keys 16*(2*ks + m) + 8*g .. +7.
+template <int D, int NQ, bool HINT>
+__device__ __forceinline__ void pv_sub(const char* vlds, int ks, const VFragAddr<D>& va, const bf16x8 (&p)[NQ][2],
+                                       f32x16 (&o)[NQ][D / 32]) {
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      const bf16x8 vf = va.read(vlds, dt, 2 * ks + m);
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) o[nq][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p[nq][m], o[nq][dt], 0, 0, 0);
     }
+  if (HINT) sched_reads_ahead_of_mfma<(D / 32) * 2, 2, NQ, 4>();
+}
+
+// Layout hint for one software-pipelined sub-step (P V of the previous sub-tile, K Q^T of the next
+// one and the softmax of the current one in a single block): a few fragment reads up front, then
+// after every matrix instruction its share of the remaining reads and of the softmax's vector
+// work, so the vector instructions issue while the matrix instruction of the same wave executes.
+template <int D, int NQ, bool HAS_V>
+__device__ __forceinline__ void sched_substep_interleave() {
+  constexpr int kMfma = (HAS_V ? (D / 32) * 2 * NQ : 0) + (D / 16) * NQ;
+  constexpr int kReads = (HAS_V ? (D / 32) * 2 * 2 : 0) + (D / 16);
+  constexpr int kAhead = HAS_V ? 6 : 3;
+  constexpr int kValu = (HAS_V ? 72 : 66) * NQ;  // rough size of one sub-tile's softmax
+  constexpr int kValuPer = (kValu + kMfma - 1) / kMfma;
+  constexpr int kReadsPer = (kReads - kAhead + kMfma - 1) / kMfma;
+  __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+  for (int i = 0; i < kMfma; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, kReadsPer, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, kValuPer, 0);
   }
 }
 

@@ -46,6 +46,9 @@ CONFIGS = {
     "dream32k": WorkloadConfig("dream32k", 4, 1, 28, 4, 32768, 128, "bf16", 128, 64, 0.1, 1, 1, 0.0, True),
     # Long-context schedule: 1024 steps, dense for the first 20 %.
     "long64k": WorkloadConfig("long64k", 5, 1, 32, 32, 65536, 128, "bf16", 128, 64, 0.05, 1024, 205, 0.02, True),
+    # Not one of the five named workloads: a short-running shape (same head dim, blocks and generator as
+    # the long-context one) for hardware-counter runs, whose 32-bit counters saturate on longer kernels.
+    "probe8k": WorkloadConfig("probe8k", 6, 1, 8, 8, 8192, 128, "bf16", 128, 64, 0.1, 1, 1, 0.0, True),
 }
 
 
