@@ -19,6 +19,7 @@
 #include "kernels.hpp"
 #include "tile_bf16.hpp"
 
+
 namespace sparsed {
 
 // EXACT_SUM: accumulate the softmax denominator from the unrounded fp32 probabilities. Used whenever
@@ -26,6 +27,7 @@ namespace sparsed {
 template <int D, int NQ, int NW, Mode MODE, bool EXACT_SUM>
 __global__ __launch_bounds__(NW * 64)
     __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? 2 : 1, (NQ == 1 && NW >= 4) ? 2 : 1))) void attn_bf16_kernel(const AttnArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64;
   constexpr int QT = 32 * NQ * NW;
   constexpr bool kHasV = MODE != Mode::kStats;
@@ -105,8 +107,12 @@ __global__ __launch_bounds__(NW * 64)
   };
   int blk0 = col_at(0), blk1 = col_at(1), blk2 = col_at(2), blk3 = col_at(3);
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
-  auto copy_k = [&](int blk, char* dst) { kdma.issue(kbase + (int64_t)uni(blk) * kTileK * a.k.sl, dst, wave); };
-  auto copy_v = [&](int blk, char* dst) { vdma.issue(vbase + (int64_t)uni(blk) * kTileK * a.v.sl, dst, wave); };
+  const int64_t slab_rows = (int64_t)(a.L - 1);
+  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
+  const __amdgpu_buffer_rsrc_t vrsrc = make_rsrc(kHasV ? vbase : kbase, kHasV ? (slab_rows * a.v.sl + D) * 2 : 0);
+  const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2), v_tile_bytes = (int32_t)(kTileK * a.v.sl * 2);
+  auto copy_k = [&](int blk, char* dst) { kdma.issue(krsrc, uni(blk) * k_tile_bytes, dst, wave); };
+  auto copy_v = [&](int blk, char* dst) { vdma.issue(vrsrc, uni(blk) * v_tile_bytes, dst, wave); };
 
   const float c = a.scale_log2;
 
@@ -261,6 +267,7 @@ __global__ __launch_bounds__(NW * 64)
         }
     }
   }
+#endif
 }
 
 int dense_qtile_bf16(int L) {

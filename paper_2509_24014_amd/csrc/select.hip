@@ -15,7 +15,8 @@ namespace sparsed {
 
 // ---------------------------------------------------------------------------- pooled scores, bf16
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void pool_bf16_kernel(const PoolArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2 ? 2 : 1, NW >= 2 ? 2 : 1))) void pool_bf16_kernel(const PoolArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64;
   constexpr int kKBytes = KLayout<D>::kTileBytes;
   __shared__ __attribute__((aligned(16))) char lds[2 * kKBytes];
@@ -43,13 +44,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   KFragAddr<D> kaddr;
   kaddr.init(lane);
   const int n_tiles = a.nkb;
-  kdma.issue(kbase, lds, wave);
+  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(a.L - 1) * a.k.sl + D) * 2);
+  const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2);
+  kdma.issue(krsrc, 0, lds, wave);
   __syncthreads();
 
   const float c = a.scale_log2;
   for (int t = 0; t < n_tiles; ++t) {
     const char* kl = lds + (t & 1) * kKBytes;
-    if (t + 1 < n_tiles) kdma.issue(kbase + (int64_t)(t + 1) * kTileK * a.k.sl, lds + ((t + 1) & 1) * kKBytes, wave);
+    if (t + 1 < n_tiles) kdma.issue(krsrc, (t + 1) * k_tile_bytes, lds + ((t + 1) & 1) * kKBytes, wave);
 
     f32x16 s0[1], s1[1];
     logits_sub<D, 1, true>(kl, 0, kaddr, qf, s0);
@@ -70,6 +73,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       arow[t] = tot * a.inv_area;
     }
   }
+#endif
 }
 
 // ---------------------------------------------------------------------------- pooled scores, fp32

@@ -136,16 +136,25 @@ struct TileDma {
       goff[u] = (int32_t)(row * stride_l * 2 + chunk * 16);
     }
   }
-  // tile: global address of the tile's first row (wave-uniform); lds_tile: LDS address of the tile.
-  __device__ __forceinline__ void issue(const __bf16* tile, char* lds_tile, int wave_in_group) const {
+  // rsrc: buffer descriptor of the (batch, head) slab; tile_byte_offset: wave-uniform byte offset of
+  // the tile's first row in it; lds_tile: LDS address of the tile. The buffer form of the direct
+  // load is used because the compiler accounts for it on the vector-memory counter only; the
+  // global_load form makes it wait for ALL outstanding LDS reads at every later use of one.
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, int32_t tile_byte_offset, char* lds_tile,
+                                        int wave_in_group) const {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
-      const char* src = reinterpret_cast<const char*>(tile) + goff[u];
       char* dst = lds_tile + lds_piece_offset(wave_in_group * kPerWave + u);
-      __builtin_amdgcn_global_load_lds((const SPARSED_GLOBAL void*)src, (SPARSED_LDS void*)dst, 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, goff[u], tile_byte_offset, 0, 0);
     }
   }
 };
+
+// Buffer descriptor over `bytes` bytes starting at base (raw dword access, no stride).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+  const int32_t n = bytes > 0x7fffffff ? 0x7fffffff : (int32_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
 
 // Q fragments of a wave: B operand of the first product. Lane (j, g) holds, for k-step kk, the 8
 // values Q[row j][16*kk + 8*g .. +7].
