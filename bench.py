@@ -42,7 +42,7 @@ def _traffic_from_profiles(workload_name):
         return None
 
 
-def cpu_baseline(cfg, q, k, v, index, keep, budget_s=20.0):
+def cpu_baseline(cfg, q, k, v, index, keep, budget_s=15.0):
     """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample of the same workload."""
     import numpy as np
 
@@ -53,22 +53,25 @@ def cpu_baseline(cfg, q, k, v, index, keep, budget_s=20.0):
     t_sparse = t_dense = 0.0
     n_sparse = n_dense = 0
     t0 = time.perf_counter()
-    heads = [int(h) for h in rng.permutation(cfg.Hq)[:4]]
+    heads = [int(h) for h in rng.permutation(cfg.Hq)]
     for h in heads:
+        if time.perf_counter() - t0 > budget_s:
+            break
         qh = q[:, h:h + 1].float().cpu()
         kh = k[:, h // group:h // group + 1].float().cpu()
         vh = v[:, h // group:h // group + 1].float().cpu()
         rp = index.row_ptr[:, h:h + 1].cpu().numpy()
         ci = index.col_idx[:, h:h + 1].cpu().numpy()
-        for I in [int(x) for x in rng.permutation(cfg.nqb)[:4]]:
+        for I in [int(x) for x in rng.permutation(cfg.nqb)[:16]]:
             if time.perf_counter() - t0 > budget_s:
                 break
             a = time.perf_counter()
             oracle.attn_sparse_rows(qh, kh, vh, rp, ci, cfg.bq, cfg.bk, 0, 0, I, I + 1)
             t_sparse += time.perf_counter() - a
             n_sparse += 1
-        if time.perf_counter() - t0 < budget_s:
-            I = int(rng.integers(cfg.nqb))
+        for I in [int(x) for x in rng.permutation(cfg.nqb)[:2]]:
+            if time.perf_counter() - t0 > budget_s:
+                break
             a = time.perf_counter()
             oracle.attn_dense_rows(qh, kh, vh, 0, 0, I * cfg.bq, (I + 1) * cfg.bq)
             t_dense += time.perf_counter() - a
@@ -126,6 +129,8 @@ def main():
                           torch.empty(cfg.B, cfg.Hq, cfg.nqb * keep, dtype=torch.int32, device=dev), cfg.bq, cfg.bk, cfg.nkb)
 
     def one_step(ev=None):
+        # the switch step of Algorithm 1: full attention (also emitting the row log-sum-exp that the
+        # selection reuses), pattern selection, then one sparse-attention call with the new pattern
         if ev:
             ev[0].record()
         sd.attn_dense(q, k, v, out=out, lse_out=lse)
@@ -138,6 +143,16 @@ def main():
         if ev:
             ev[3].record()
 
+    def time_call(fn, reps):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -147,10 +162,14 @@ def main():
         one_step(events[i])
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    dense_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    dense_lse_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     select_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
     sparse_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
     ms_per_step = wall_ms / args.steps
+    # the dense call of an ordinary (non-switch) step does not emit the log-sum-exp
+    dense_ms = time_call(lambda: sd.attn_dense(q, k, v, out=out), max(1, min(args.steps, 5)))
+    # selection when the caller has no log-sum-exp to hand over (own statistics pass included)
+    select_alone_ms = time_call(lambda: sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, workspace=ws, index=index), 1)
 
     f_dense, f_select, f_sparse = _flops(cfg, keep)
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
@@ -200,7 +219,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "L": cfg.L, "d": cfg.d,
                    "block_q": cfg.bq, "block_k": cfg.bk, "rho": cfg.rho, "kept_blocks": keep, "step": "dense+select+sparse"},
-        "ms_per_call": {"dense": dense_ms, "select": select_ms, "sparse": sparse_ms},
+        "ms_per_call": {"dense": dense_ms, "dense_with_lse": dense_lse_ms, "select": select_ms,
+                        "select_with_own_statistics": select_alone_ms, "sparse": sparse_ms},
         "tflops": {"dense": dense_tf, "select_one_qkT": select_tf, "sparse_executed": sparse_tf,
                    "sparse_dense_equivalent": tf(f_dense, sparse_ms)},
         "pct_of_peak": {"dense": 100 * dense_tf / peak, "sparse_executed": 100 * sparse_tf / peak, "select_one_qkT": 100 * select_tf / peak},

@@ -22,9 +22,7 @@
 
 namespace sparsed {
 
-// EXACT_SUM: accumulate the softmax denominator from the unrounded fp32 probabilities. Used whenever
-// the row log-sum-exp is an output (pattern selection needs it to ~1e-7), at one more VALU op per key.
-template <int D, int NQ, int NW, Mode MODE, bool EXACT_SUM>
+template <int D, int NQ, int NW, Mode MODE>
 __global__ __launch_bounds__(NW * 64)
     __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? 2 : 1, (NQ == 1 && NW >= 4) ? 2 : 1))) void attn_bf16_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
@@ -135,7 +133,6 @@ __global__ __launch_bounds__(NW * 64)
       any_raise = any_raise || (__builtin_amdgcn_ballot_w64(raise) != 0);
       M[nq] = Mn;
       float part = 0.f;
-      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int m = 0; m < 2; ++m) {
         u32x4 pk;
@@ -143,16 +140,12 @@ __global__ __launch_bounds__(NW * 64)
         for (int x = 0; x < 8; x += 2) {
           const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x], c, -Mn)),
                              __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x + 1], c, -Mn))};
-          if (kHasV) {
-            const bf16x2 r = __builtin_convertvector(two, bf16x2);
-            pk[x >> 1] = __builtin_bit_cast(uint32_t, r);
-            // row sum over the ROUNDED values: numerator and denominator see the same probabilities
-            if (!EXACT_SUM) part = __builtin_amdgcn_fdot2_f32_bf16(r, ones, part, false);
-          }
-          if (EXACT_SUM || !kHasV) {
-            part += two[0];
-            part += two[1];
-          }
+          if (kHasV) pk[x >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
+          // The denominator is summed from the unrounded fp32 probabilities with plain adds: the row
+          // log-sum-exp that pattern selection reuses needs it to ~1e-7, and the packed bf16 dot
+          // instruction, one op cheaper, runs on the matrix pipe and stalls the MFMAs it overlaps.
+          part += two[0];
+          part += two[1];
         }
         if (kHasV) {
           // pin: the probabilities must exist HERE, inside the block that holds the matrix
@@ -282,16 +275,7 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.n_qtiles;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)total), block(NW * 64);
-  if constexpr (MODE == Mode::kStats) {
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, true>), grid, block, 0, s, a);
-  } else if constexpr (MODE == Mode::kDense) {
-    if (a.lse != nullptr)
-      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, true>), grid, block, 0, s, a);
-    else
-      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, false>), grid, block, 0, s, a);
-  } else {
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, false>), grid, block, 0, s, a);
-  }
+  hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 

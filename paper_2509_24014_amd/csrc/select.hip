@@ -14,15 +14,34 @@
 namespace sparsed {
 
 // ---------------------------------------------------------------------------- pooled scores, bf16
+// Sum of one value per lane over the 64 lanes of a wave with DPP row operations (no LDS traffic);
+// the total ends up in lane 63.
+__device__ __forceinline__ float wave_sum_to_last_lane(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x111, 0xf, 0xf, true));  // row_shr:1
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x112, 0xf, 0xf, true));  // row_shr:2
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x114, 0xf, 0xf, true));  // row_shr:4
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x118, 0xf, 0xf, true));  // row_shr:8
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xa, 0xf, true));  // row_bcast:15
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143, 0xc, 0xf, true));  // row_bcast:31
+  return x;
+}
+
+// One work-group (NW waves, 32 query rows each) per query block. Same 32-key software pipeline as
+// the attention kernels: sub-step u interleaves the matrix work S(u+1) = K(u+1) Q^T with the vector
+// work of sub-tile u (p = 2^(s*c - lse), summed per lane). A key block is two sub-tiles; its
+// per-lane sums are reduced over the wave, then over the waves through LDS in a fixed order.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2 ? 2 : 1, NW >= 2 ? 2 : 1))) void pool_bf16_kernel(const PoolArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2 ? 2 : 1, NW >= 2 ? 2 : 1)))
+void pool_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64;
   constexpr int kKBytes = KLayout<D>::kTileBytes;
-  __shared__ __attribute__((aligned(16))) char lds[2 * kKBytes];
+  __shared__ __attribute__((aligned(1024))) char kbuf0[kKBytes];
+  __shared__ __attribute__((aligned(1024))) char kbuf1[kKBytes];
   __shared__ float wsum[2][NW];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 31;
   const int lid = xcd_remap(blockIdx.x, gridDim.x);
   const int I = lid % a.nqb;
@@ -43,36 +62,77 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2
   kdma.init(a.k.sl, wave, lane);
   KFragAddr<D> kaddr;
   kaddr.init(lane);
-  const int n_tiles = a.nkb;
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(a.L - 1) * a.k.sl + D) * 2);
   const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2);
-  kdma.issue(krsrc, 0, lds, wave);
-  __syncthreads();
-
+  const int n = a.nkb;
   const float c = a.scale_log2;
-  for (int t = 0; t < n_tiles; ++t) {
-    const char* kl = lds + (t & 1) * kKBytes;
-    if (t + 1 < n_tiles) kdma.issue(krsrc, (t + 1) * k_tile_bytes, lds + ((t + 1) & 1) * kKBytes, wave);
 
-    f32x16 s0[1], s1[1];
-    logits_sub<D, 1, true>(kl, 0, kaddr, qf, s0);
-    logits_sub<D, 1, true>(kl, 1, kaddr, qf, s1);
+  f32x16 s_even[1], s_odd[1];
+  float carry = 0.f;  // per-lane sum of the even sub-tile of the key block in progress
+  auto expsum_sub = [&](f32x16(&s)[1]) -> float {
     float part = 0.f;
 #pragma unroll
-    for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s0[0][x], c, -lse2));
-#pragma unroll
-    for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s1[0][x], c, -lse2));
-    part = wave_sum(part);
-    if (lane == 0) wsum[t & 1][wave] = part;
-
-    __syncthreads();
+    for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][x], c, -lse2));
+    asm volatile("" : "+v"(part));  // keep the vector work inside the block that holds the matrix work
+    return part;
+  };
+  auto flush_block = [&](int t, float part) {  // after the tile barrier: key block t is complete
+    (void)part;
     if (tid == 0) {
       float tot = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) tot += wsum[t & 1][w];
       arow[t] = tot * a.inv_area;
     }
+  };
+
+  // Tile step t (LDS parity P = t & 1) = sub-steps 2t+1 and 2t+2. On entry S(2t+1) is in s_odd, the
+  // per-lane sum of sub-tile 2t in `carry`, K(t+1) in kbuf[1-P]; kbuf[P] is free and receives K(t+2).
+#define SPARSED_POOL_STEP(P, STEADY, T)                                                            \
+  {                                                                                                \
+    char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
+    char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
+    const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
+    const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
+    if (has_k2) kdma.issue(krsrc, ((T) + 2) * k_tile_bytes, kb_free, wave);                        \
+    if (has_next) logits_sub<D, 1, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                      \
+    float part = carry + expsum_sub(s_odd);                                                        \
+    if (STEADY) sched_substep_interleave<D, 1, false>();                                           \
+    part = wave_sum_to_last_lane(part);                                                            \
+    if (lane == 63) wsum[(P)][wave] = part;                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                             \
+    if (has_next) {                                                                                \
+      logits_sub<D, 1, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                                   \
+      carry = expsum_sub(s_even);                                                                  \
+      if (STEADY) sched_substep_interleave<D, 1, false>();                                         \
+    }                                                                                              \
+    __syncthreads();                                                                               \
+    flush_block((T), part);                                                                        \
   }
+
+  // prologue: K(0), K(1) into LDS; S(0); then sub-step 0: S(1) alongside the sums of sub-tile 0
+  kdma.issue(krsrc, 0, kbuf0, wave);
+  if (n > 1) kdma.issue(krsrc, k_tile_bytes, kbuf1, wave);
+  __syncthreads();
+  logits_sub<D, 1, true>(kbuf0, 0, kaddr, qf, s_even);
+  logits_sub<D, 1, true>(kbuf0, 1, kaddr, qf, s_odd);
+  carry = expsum_sub(s_even);
+  __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
+
+  int t = 0;
+  while (t + 3 < n) {
+    SPARSED_POOL_STEP(0, true, t);
+    SPARSED_POOL_STEP(1, true, t + 1);
+    t += 2;
+  }
+  for (; t < n; ++t) {
+    if (t & 1) {
+      SPARSED_POOL_STEP(1, false, t);
+    } else {
+      SPARSED_POOL_STEP(0, false, t);
+    }
+  }
+#undef SPARSED_POOL_STEP
 #endif
 }
 
