@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-schedule", action="store_true", help="skip the full T-step schedule run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE runs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards by head with no exchange; "
@@ -153,6 +155,12 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
