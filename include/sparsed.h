@@ -21,7 +21,8 @@
  *  - Tensors are [B, H, L, D] views with arbitrary element strides for B, H, L
  *    and unit stride for D. `data` must be 16-byte aligned and every stride a
  *    multiple of 8 elements (bf16) or 4 elements (fp32), so that every row is
- *    16-byte aligned.
+ *    16-byte aligned. One (batch, head) slab, (L-1)*stride_l + D elements, must
+ *    span less than 2^31 bytes.
  *  - Grouped-query attention: q has Hq heads, k and v have Hkv heads with
  *    Hq % Hkv == 0; query head h reads key/value head h / (Hq / Hkv).
  *  - Supported shapes: D in {64, 128}; L a multiple of 64 (bf16) or 32 (fp32);

@@ -45,6 +45,10 @@ sparsed_status check_tensor(const sparsed_tensor* t, const char* name) {
   if (t->stride_l < t->D || t->stride_l % al || t->stride_h % al || t->stride_b % al || t->stride_h < 0 || t->stride_b < 0)
     return fail(SPARSED_ERR_STRIDE, "%s: strides (%lld,%lld,%lld) must be multiples of %d elements and stride_l >= D", name,
                 (long long)t->stride_b, (long long)t->stride_h, (long long)t->stride_l, al);
+  // one (batch, head) slab is addressed with 32-bit byte offsets inside the kernels
+  const int64_t slab_bytes = ((int64_t)(t->L - 1) * t->stride_l + t->D) * (t->dtype == SPARSED_BF16 ? 2 : 4);
+  if (slab_bytes >= ((int64_t)1 << 31))
+    return fail(SPARSED_ERR_STRIDE, "%s: one (batch, head) slab spans %lld bytes, the limit is 2^31", name, (long long)slab_bytes);
   return SPARSED_OK;
 }
 

@@ -270,16 +270,18 @@ __device__ __forceinline__ void pv_sub(const char* vlds, int ks, const VFragAddr
 // work, so the vector instructions issue while the matrix instruction of the same wave executes.
 template <int D, int NQ, bool HAS_V>
 __device__ __forceinline__ void sched_substep_interleave() {
+  constexpr int G = 1;  // matrix instructions per group (coarser groups measured no better)
   constexpr int kMfma = (HAS_V ? (D / 32) * 2 * NQ : 0) + (D / 16) * NQ;
   constexpr int kReads = (HAS_V ? (D / 32) * 2 * 2 : 0) + (D / 16);
   constexpr int kAhead = HAS_V ? 6 : 3;
   constexpr int kValu = (HAS_V ? 72 : 66) * NQ;  // rough size of one sub-tile's softmax
-  constexpr int kValuPer = (kValu + kMfma - 1) / kMfma;
-  constexpr int kReadsPer = (kReads - kAhead + kMfma - 1) / kMfma;
+  constexpr int kGroups = kMfma / G;
+  constexpr int kValuPer = (kValu + kGroups - 1) / kGroups;
+  constexpr int kReadsPer = (kReads - kAhead + kGroups - 1) / kGroups;
   __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-  for (int i = 0; i < kMfma; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+  for (int i = 0; i < kGroups; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, G, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, kReadsPer, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, kValuPer, 0);
   }

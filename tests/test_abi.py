@@ -68,6 +68,8 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_attn_dense(R(_t(H=3)), R(k), R(v), R(_t(H=3)), None) == 2           # 3 % 2 != 0
     assert lib.sparsed_attn_dense(R(_t(data=0x1004)), R(k), R(v), R(o), None) == 4         # alignment
     assert lib.sparsed_attn_dense(R(_t(sl=66)), R(k), R(v), R(o), None) == 4               # stride
+    big = _t(L=1 << 20, sl=1 << 12)                                                        # slab of 2^34 bytes
+    assert lib.sparsed_attn_dense(R(big), R(big), R(big), R(big), None) == 4
     assert lib.sparsed_attn_dense(R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), None) == 2   # L % 32
     assert b"L 48" in lib.sparsed_last_error()
     ix = _ix()
