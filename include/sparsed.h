@@ -149,6 +149,24 @@ sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sp
                                                sparsed_block_index* out_block_index,
                                                const sparsed_exec* ex);
 
+/*
+ * Fixed pattern of the paper's sparse baselines (Section 4.1: sliding window, and
+ * StreamingLLM = window + leading "sink" keys) written as a block index, so the
+ * same sparse kernel runs them: query block I keeps every key block holding a
+ * key j with |i - j| <= window_tokens/2 for one of its queries i (the window is
+ * taken symmetric because attention here is bidirectional), plus the key blocks
+ * that overlap the first sink_tokens keys. The same rows for every head; rows
+ * have different lengths. idx->B, H, nqb, nkb, block_q, block_k must describe a
+ * sequence of seq_len tokens; cap_per_head must be >=
+ * sparsed_index_window_entries(...), else SPARSED_ERR_INDEX.
+ */
+sparsed_status sparsed_index_fill_window(sparsed_block_index* idx, int32_t seq_len, int32_t window_tokens,
+                                         int32_t sink_tokens, const sparsed_exec* ex);
+
+/* col_idx entries per head that sparsed_index_fill_window writes (-1 on bad arguments). Host only. */
+int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t block_k, int32_t window_tokens,
+                                     int32_t sink_tokens);
+
 /* "Top rho%" of n blocks: ceil(rho*n - 1e-9) clamped to [1, n]; 0 if n <= 0. Host only. */
 int32_t sparsed_kept_blocks(double rho, int32_t n);
 

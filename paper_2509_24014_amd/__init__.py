@@ -4,7 +4,9 @@ from .binding import (  # noqa: F401
     SparsedError,
     attn_dense,
     attn_sparse,
+    index_fill_window,
     index_validate,
+    index_window_entries,
     kept_blocks,
     load_library,
     n_dense_steps,

@@ -23,6 +23,7 @@ EXPORTS = [
     "sparsed_attn_dense", "sparsed_select_pattern", "sparsed_attn_sparse", "sparsed_select_pattern_isolated",
     "sparsed_kept_blocks", "sparsed_n_dense_steps", "sparsed_select_workspace_bytes", "sparsed_index_validate",
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
+    "sparsed_index_fill_window", "sparsed_index_window_entries",
 ]
 
 
@@ -81,6 +82,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_select_workspace_bytes.restype = ctypes.c_size_t
     lib.sparsed_index_validate.argtypes = [I, E]
     lib.sparsed_index_validate.restype = ctypes.c_int
+    lib.sparsed_index_fill_window.argtypes = [I, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, E]
+    lib.sparsed_index_fill_window.restype = ctypes.c_int
+    lib.sparsed_index_window_entries.argtypes = [ctypes.c_int32] * 5
+    lib.sparsed_index_window_entries.restype = ctypes.c_int64
     lib.sparsed_status_string.argtypes = [ctypes.c_int]
     lib.sparsed_status_string.restype = ctypes.c_char_p
     lib.sparsed_last_error.argtypes = []
@@ -233,6 +238,25 @@ def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, 
     _check(lib.sparsed_attn_sparse(ctypes.byref(tq), ctypes.byref(tk), ctypes.byref(tv), ctypes.byref(ci), ctypes.byref(to),
                                    ctypes.byref(ex)))
     return out
+
+
+def index_window_entries(seq_len: int, block_q: int, block_k: int, window_tokens: int, sink_tokens: int) -> int:
+    return int(load_library().sparsed_index_window_entries(seq_len, block_q, block_k, window_tokens, sink_tokens))
+
+
+def index_fill_window(B: int, H: int, seq_len: int, block_q: int, block_k: int, window_tokens: int, sink_tokens: int,
+                      device, stream=None) -> BlockIndex:
+    """sparsed_index_fill_window: sliding-window (+ sink) pattern as a block index for attn_sparse."""
+    lib = load_library()
+    cap = index_window_entries(seq_len, block_q, block_k, window_tokens, sink_tokens)
+    if cap < 0:
+        raise SparsedError(5, "bad window pattern arguments")
+    index = BlockIndex(torch.empty(B, H, seq_len // block_q + 1, dtype=torch.int32, device=device),
+                       torch.empty(B, H, max(cap, 1), dtype=torch.int32, device=device), block_q, block_k, seq_len // block_k)
+    ex = _Exec(_stream_ptr(stream), None, 0, None, None, None)
+    ci = index._c()
+    _check(lib.sparsed_index_fill_window(ctypes.byref(ci), seq_len, window_tokens, sink_tokens, ctypes.byref(ex)))
+    return index
 
 
 def index_validate(index: BlockIndex, stream=None) -> None:

@@ -329,6 +329,50 @@ sparsed_status sparsed_index_validate(const sparsed_block_index* ix, const spars
   return SPARSED_OK;
 }
 
+sparsed_status sparsed_index_fill_window(sparsed_block_index* ix, int32_t seq_len, int32_t window_tokens, int32_t sink_tokens,
+                                         const sparsed_exec* ex) {
+  if (!ix) return fail(SPARSED_ERR_NULL, "block index is NULL");
+  if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
+  if (ix->B <= 0 || ix->H <= 0 || ix->block_q <= 0 || ix->block_k <= 0 || seq_len <= 0 || seq_len % ix->block_q ||
+      seq_len % ix->block_k || ix->nqb != seq_len / ix->block_q || ix->nkb != seq_len / ix->block_k)
+    return fail(SPARSED_ERR_INDEX, "block index does not describe a sequence of %d tokens", seq_len);
+  if (window_tokens < 0 || sink_tokens < 0) return fail(SPARSED_ERR_RANGE, "negative window or sink length");
+  WindowArgs a{};
+  a.row_ptr = ix->row_ptr;
+  a.col_idx = ix->col_idx;
+  a.heads = ix->B * ix->H;
+  a.nqb = ix->nqb;
+  a.nkb = ix->nkb;
+  a.block_q = ix->block_q;
+  a.block_k = ix->block_k;
+  a.L = seq_len;
+  a.cap_per_head = ix->cap_per_head;
+  a.half_window = window_tokens / 2;
+  a.sink_blocks = (sink_tokens + ix->block_k - 1) / ix->block_k;
+  int64_t total = 0;
+  for (int I = 0; I < ix->nqb; ++I) {
+    int first, last;
+    window_block_range(I, a.block_q, a.block_k, a.L, a.half_window, &first, &last);
+    total += (a.sink_blocks < first ? a.sink_blocks : first) + (last - first + 1);
+  }
+  if (total > ix->cap_per_head) return fail(SPARSED_ERR_INDEX, "cap_per_head %d < %lld entries the pattern needs", ix->cap_per_head, (long long)total);
+  const hipError_t e = launch_window_index(a, stream_of(ex));
+  if (e != hipSuccess) return hip_fail(e, "window index launch");
+  return SPARSED_OK;
+}
+
+int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t block_k, int32_t window_tokens, int32_t sink_tokens) {
+  if (seq_len <= 0 || block_q <= 0 || block_k <= 0 || seq_len % block_q || seq_len % block_k || window_tokens < 0 || sink_tokens < 0) return -1;
+  const int sink_blocks = (sink_tokens + block_k - 1) / block_k;
+  int64_t total = 0;
+  for (int I = 0; I < seq_len / block_q; ++I) {
+    int first, last;
+    window_block_range(I, block_q, block_k, seq_len, window_tokens / 2, &first, &last);
+    total += (sink_blocks < first ? sink_blocks : first) + (last - first + 1);
+  }
+  return total;
+}
+
 const char* sparsed_status_string(sparsed_status s) {
   switch (s) {
     case SPARSED_OK: return "ok";

@@ -55,6 +55,15 @@ struct ValidateArgs {
   int32_t* bad;            // device counter of malformed rows
 };
 
+// Arguments of the fixed-pattern index builder (sliding window + attention sinks).
+struct WindowArgs {
+  int32_t* row_ptr;
+  int32_t* col_idx;
+  int32_t heads, nqb, nkb, block_q, block_k, L, cap_per_head;
+  int32_t half_window;  // tokens on either side of a query that stay visible
+  int32_t sink_blocks;  // leading key blocks that are always visible
+};
+
 enum class Mode : int { kDense = 0, kSparse = 1, kStats = 2 };
 
 // Launchers. Each returns the HIP error of the launch. block_q selects the work-group shape for
@@ -65,6 +74,15 @@ hipError_t launch_pool_bf16(int D, int block_q, const PoolArgs& a, hipStream_t s
 hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);
+hipError_t launch_window_index(const WindowArgs& a, hipStream_t s);
+// Key blocks [first, last] that the window of query block I touches (shared by host sizing and the kernel).
+__host__ __device__ inline void window_block_range(int I, int block_q, int block_k, int L, int half_window, int* first, int* last) {
+  long lo = (long)I * block_q - half_window, hi = (long)(I + 1) * block_q - 1 + half_window;
+  if (lo < 0) lo = 0;
+  if (hi > L - 1) hi = L - 1;
+  *first = (int)(lo / block_k);
+  *last = (int)(hi / block_k);
+}
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
 
 // Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).

@@ -270,6 +270,30 @@ __global__ __launch_bounds__(256) void validate_kernel(const ValidateArgs a) {
   if (!ok) atomicAdd(a.bad, 1);
 }
 
+// ---------------------------------------------------------------------------- fixed patterns
+// Sliding window plus attention sinks as a block index (the fixed patterns the paper compares
+// against, Section 4.1): query block I keeps the leading `sink_blocks` key blocks and every key
+// block that holds a key within `half_window` tokens of one of its queries. One thread per row.
+__global__ __launch_bounds__(256) void window_index_kernel(const WindowArgs a) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= a.heads * a.nqb) return;
+  const int bh = r / a.nqb, I = r % a.nqb;
+  int offset = 0, first = 0, last = 0;
+  for (int i = 0; i <= I; ++i) {
+    window_block_range(i, a.block_q, a.block_k, a.L, a.half_window, &first, &last);
+    const int sinks = a.sink_blocks < first ? a.sink_blocks : first;
+    if (i < I) offset += sinks + (last - first + 1);
+  }
+  const int sinks = a.sink_blocks < first ? a.sink_blocks : first;
+  int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1);
+  int32_t* ci = a.col_idx + (int64_t)bh * a.cap_per_head + offset;
+  int n = 0;
+  for (int J = 0; J < sinks; ++J) ci[n++] = J;
+  for (int J = first; J <= last; ++J) ci[n++] = J;
+  rp[I] = offset;
+  if (I == a.nqb - 1) rp[a.nqb] = offset + n;
+}
+
 // ---------------------------------------------------------------------------- launchers
 template <int D>
 static hipError_t launch_pool_bf16_d(int block_q, const PoolArgs& a, hipStream_t s) {
@@ -314,6 +338,13 @@ hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s)
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s) {
   if (a.rows <= 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.rows), dim3(64), (size_t)a.nkb * sizeof(uint32_t), s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_window_index(const WindowArgs& a, hipStream_t s) {
+  const int rows = a.heads * a.nqb;
+  if (rows <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(window_index_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -247,6 +247,48 @@ def test_closed_form_w1_embedded_in_head_dim_64():
     got = sd.attn_dense(*_dev(q, k, v))
     np.testing.assert_allclose(got.cpu().double().numpy()[0, 0, rows, 0], g["dense"], atol=1e-5)
 
+# ----------------------------------------------------------------------------- fixed patterns (Section 4.1 baselines)
+@pytest.mark.parametrize("L,bq,bk,window,sink", [
+    (1024, 128, 64, 256, 0),      # sliding window
+    (1024, 128, 64, 256, 64),     # window + one sink block
+    (512, 32, 64, 100, 70),       # query blocks smaller than key blocks, sinks straddle a block edge
+    (512, 64, 64, 0, 0),          # diagonal only
+    (512, 64, 64, 4096, 0),       # window wider than the sequence: every block
+    (2048, 64, 32, 300, 33),      # fp32 block shape, many rows
+])
+def test_window_index_matches_token_level_definition(L, bq, bk, window, sink):
+    from oracle import patterns
+    _say(f"window index L={L} {bq}x{bk} window={window} sink={sink}")
+    H = 3
+    rows = patterns.window_block_rows(L, bq, bk, window, sink)
+    ptr, col = patterns.rows_to_csr(rows, H)
+    assert sd.index_window_entries(L, bq, bk, window, sink) == col.shape[1]
+    ix = sd.index_fill_window(1, H, L, bq, bk, window, sink, DEV)
+    sd.index_validate(ix)
+    assert np.array_equal(ix.row_ptr.cpu().numpy().reshape(H, -1), ptr)
+    assert np.array_equal(ix.col_idx.cpu().numpy().reshape(H, -1)[:, :col.shape[1]], col)
+
+
+def test_window_index_feeds_the_sparse_kernel():
+    from oracle import patterns
+    L, bq, bk, H = 1024, 128, 64, 2
+    q, k, v = _rand_qkv(1, H, H, L, 128, torch.bfloat16, seed=77)
+    ix = sd.index_fill_window(1, H, L, bq, bk, 256, 64, DEV)
+    got = sd.attn_sparse(*_dev(q, k, v), ix)
+    ptr, col = patterns.rows_to_csr(patterns.window_block_rows(L, bq, bk, 256, 64), H)
+    want = oracle.attn_sparse(q, k, v, ptr[None], col[None], bq, bk)
+    assert_output_close(got, want, torch.bfloat16, "window + sink sparse")
+
+
+def test_window_index_rejects_small_capacity():
+    ix = sd.BlockIndex(torch.zeros(1, 1, 9, dtype=torch.int32, device=DEV), torch.zeros(1, 1, 8, dtype=torch.int32, device=DEV), 64, 64, 8)
+    import ctypes
+    from paper_2509_24014_amd import binding
+    ci = ix._c()
+    st = binding.load_library().sparsed_index_fill_window(ctypes.byref(ci), 512, 256, 0, None)
+    assert st == 8 and b"cap_per_head" in binding.load_library().sparsed_last_error()
+    assert int(ix.row_ptr.abs().sum()) == 0       # nothing was launched
+
 
 # ----------------------------------------------------------------------------- the tiny schedule, in full
 def test_tiny_config_full_schedule():
@@ -276,6 +318,40 @@ def test_tiny_config_full_schedule():
         assert_output_close(got, want, torch.float32, f"tiny step {t}")
         inp.advance()
     assert layer.calls == {"dense": 1, "select": 1, "sparse": 4}
+
+
+def test_schedule_ablation_modes_against_oracle():
+    """Two of Table 2's ablations as the driver runs them: no dense steps (select at step 0 from that
+    step's own q, k), and a fresh selection at every sparse step."""
+    cfg = workload.get_config("tiny")
+    keep = oracle.kept_blocks(cfg.rho, cfg.nkb)
+    for mode in ("no_skip", "reselect"):
+        inp = workload.make_inputs(cfg, seed=3, device="cpu")
+        layer = (sd.SparseDLayer(cfg.T, 0.2, cfg.bq, cfg.bk, cfg.rho, n_dense=0) if mode == "no_skip"
+                 else sd.SparseDLayer(cfg.T, 0.2, cfg.bq, cfg.bk, cfg.rho, reselect_every_step=True))
+        first_index = None
+        for t in range(cfg.T):
+            q, k, v = inp.rounded()
+            got = layer.step(*_dev(q, k, v), t)
+            if t < layer.n_dense:
+                want = oracle.attn_dense(q, k, v)
+            else:
+                selected_now = (mode == "reselect") or t == 0
+                if selected_now:
+                    _, ci, apool, _ = oracle.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho)
+                    compare_index(layer.index.col_idx.cpu().numpy(), ci, apool.reshape(-1, cfg.nkb), keep)
+                if first_index is None:
+                    first_index = layer.index.col_idx.clone()
+                elif mode == "no_skip":
+                    assert torch.equal(layer.index.col_idx, first_index)
+                want = oracle.attn_sparse(q, k, v, layer.index.row_ptr.cpu().numpy(), layer.index.col_idx.cpu().numpy(), cfg.bq, cfg.bk)
+            assert_output_close(got, want, torch.float32, f"{mode} step {t}")
+            inp.advance()
+        _say(f"ablation {mode}: calls {layer.calls}")
+        if mode == "no_skip":
+            assert layer.calls == {"dense": 0, "select": 1, "sparse": cfg.T}
+        else:
+            assert layer.calls["select"] >= cfg.T - layer.n_dense
 
 
 # ----------------------------------------------------------------------------- named workloads at full size
