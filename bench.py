@@ -240,6 +240,15 @@ def main():
         "roofline_select": {"kernel": "select_pattern (pooled scores + top-k, statistics reused)", "bound": "mfma",
                             "achieved": select_tf, "peak": peak, "unit": "TFLOP/s", "frac": select_tf / peak},
     }
+    if cfg.dtype == "bf16":
+        # What the matrix cores sustain on their own (no LDS, no vector work): all-zero operands reach the published
+        # peak, operands with random signs and mantissas make the chip settle at a lower clock. The second figure is
+        # the ceiling for any kernel that multiplies real data; `frac` above stays relative to the published peak.
+        zero_tf, rand_tf = sd.probe_mfma_bf16(False), sd.probe_mfma_bf16(True)
+        result["mfma_rate_measured"] = {"unit": "TFLOP/s", "zero_operands": zero_tf, "random_operands": rand_tf,
+                                        "kernel": "bf16 32x32x16 matrix instructions only, operands in registers"}
+        for key, val in (("roofline", sparse_tf), ("roofline_dense", dense_tf), ("roofline_select", select_tf)):
+            result[key]["frac_of_measured_rate_random_operands"] = val / rand_tf
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, index, keep)
     print(json.dumps(result))

@@ -188,6 +188,17 @@ size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, 
  */
 sparsed_status sparsed_index_validate(const sparsed_block_index* idx, const sparsed_exec* ex);
 
+/*
+ * Diagnostic, not part of the method: the rate (TFLOP/s) this GPU sustains on bf16 32x32x16 matrix
+ * instructions alone, operands in registers, 8 waves on every compute unit for `iters` x 32
+ * instructions per wave. random_operands == 0 uses all-zero operands (reaches the published peak);
+ * != 0 uses operands with random signs and mantissas, for which the chip settles at a lower clock:
+ * the practical ceiling for kernels that multiply real data. SYNCHRONISES the stream. Uses
+ * ex->workspace (512 KiB) if given, else the library's own buffer.
+ */
+sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out,
+                                       const sparsed_exec* ex);
+
 const char* sparsed_status_string(sparsed_status s);
 const char* sparsed_last_error(void); /* thread-local, never NULL */
 int32_t sparsed_version(void);

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     index_fill_window,
     index_validate,
     index_window_entries,
+    probe_mfma_bf16,
     kept_blocks,
     load_library,
     n_dense_steps,

@@ -23,7 +23,7 @@ EXPORTS = [
     "sparsed_attn_dense", "sparsed_select_pattern", "sparsed_attn_sparse", "sparsed_select_pattern_isolated",
     "sparsed_kept_blocks", "sparsed_n_dense_steps", "sparsed_select_workspace_bytes", "sparsed_index_validate",
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
-    "sparsed_index_fill_window", "sparsed_index_window_entries",
+    "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16",
 ]
 
 
@@ -86,6 +86,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_index_fill_window.restype = ctypes.c_int
     lib.sparsed_index_window_entries.argtypes = [ctypes.c_int32] * 5
     lib.sparsed_index_window_entries.restype = ctypes.c_int64
+    lib.sparsed_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), E]
+    lib.sparsed_probe_mfma_bf16.restype = ctypes.c_int
     lib.sparsed_status_string.argtypes = [ctypes.c_int]
     lib.sparsed_status_string.restype = ctypes.c_char_p
     lib.sparsed_last_error.argtypes = []
@@ -238,6 +240,13 @@ def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, 
     _check(lib.sparsed_attn_sparse(ctypes.byref(tq), ctypes.byref(tk), ctypes.byref(tv), ctypes.byref(ci), ctypes.byref(to),
                                    ctypes.byref(ex)))
     return out
+
+
+def probe_mfma_bf16(random_operands: bool, iters: int = 20000) -> float:
+    """sparsed_probe_mfma_bf16: sustained TFLOP/s of bf16 matrix instructions alone (diagnostic)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().sparsed_probe_mfma_bf16(1 if random_operands else 0, iters, ctypes.byref(out), None))
+    return out.value
 
 
 def index_window_entries(seq_len: int, block_q: int, block_k: int, window_tokens: int, sink_tokens: int) -> int:

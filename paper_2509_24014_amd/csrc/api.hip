@@ -373,6 +373,38 @@ int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t b
   return total;
 }
 
+sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out, const sparsed_exec* ex) {
+  if (!tflops_out) return fail(SPARSED_ERR_NULL, "tflops_out is NULL");
+  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
+  void* scratch = nullptr;
+  const size_t need = (size_t)kProbeFloats * sizeof(float);
+  if (ex && ex->workspace) {
+    if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "probe needs %zu bytes of workspace", need);
+    scratch = ex->workspace;
+  } else {
+    const sparsed_status st = own_workspace(need, &scratch);
+    if (st != SPARSED_OK) return st;
+  }
+  hipStream_t s = stream_of(ex);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = launch_mfma_rate(static_cast<float*>(scratch), iters / 8 + 1, random_operands, s);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(t0, s);
+  if (e == hipSuccess) e = launch_mfma_rate(static_cast<float*>(scratch), iters, random_operands, s);
+  if (e == hipSuccess) e = hipEventRecord(t1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  if (e != hipSuccess) return hip_fail(e, "matrix-core rate probe");
+  // waves x MFMAs per iteration x flops per 32x32x16 MFMA
+  const double flops = (double)kProbeGroups * 8.0 * 32.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
+  *tflops_out = ms > 0.f ? flops / ((double)ms * 1e9) : 0.0;
+  return SPARSED_OK;
+}
+
 const char* sparsed_status_string(sparsed_status s) {
   switch (s) {
     case SPARSED_OK: return "ok";

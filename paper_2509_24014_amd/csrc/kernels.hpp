@@ -83,6 +83,10 @@ __host__ __device__ inline void window_block_range(int I, int block_q, int block
   *first = (int)(lo / block_k);
   *last = (int)(hi / block_k);
 }
+// Matrix-core rate probe: kProbeGroups work-groups x 8 waves, each wave issues 32 MFMAs per iteration.
+constexpr int kProbeGroups = 256;
+constexpr int kProbeFloats = kProbeGroups * 512;
+hipError_t launch_mfma_rate(float* scratch, int iters, int random_operands, hipStream_t s);
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
 
 // Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).
