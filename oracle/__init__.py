@@ -114,23 +114,19 @@ def attn_dense_rows(q, k, v, b: int, h: int, i0: int, i1: int) -> np.ndarray:
 
 
 def pool_scores(q, k, bq: int, bk: int) -> np.ndarray:
-    """A' = avgpool(A, bq x bk) -> float64 [B, Hq, L/bq, L/bk]."""
+    """A' = avgpool(A, bq x bk) -> float64 [B, Hq, ceil(L/bq), ceil(L/bk)] (partial last blocks: mean of what exists)."""
     q, k = _f32(q), _f32(k)
     B, Hq, Hkv, L, d = _dims(q, k)
-    if L % bq or L % bk:
-        raise ValueError("L must be a multiple of both block sizes")
-    ap = np.empty((B, Hq, L // bq, L // bk), dtype=np.float64)
+    ap = np.empty((B, Hq, -(-L // bq), -(-L // bk)), dtype=np.float64)
     _check(_load().oracle_pool_scores(_p(q), _p(k), B, Hq, Hkv, L, d, bq, bk, _p(ap)), "pool_scores")
     return ap
 
 
 def pool_scores_rows(q, k, bq: int, bk: int, b: int, h: int, I0: int, I1: int) -> np.ndarray:
-    """A' rows for query blocks [I0, I1) of one (b, h) -> float64 [I1-I0, L/bk]."""
+    """A' rows for query blocks [I0, I1) of one (b, h) -> float64 [I1-I0, ceil(L/bk)]."""
     q, k = _f32(q), _f32(k)
     B, Hq, Hkv, L, d = _dims(q, k)
-    if L % bq or L % bk:
-        raise ValueError("L must be a multiple of both block sizes")
-    ap = np.empty((I1 - I0, L // bk), dtype=np.float64)
+    ap = np.empty((I1 - I0, -(-L // bk)), dtype=np.float64)
     _check(_load().oracle_pool_scores_rows(_p(q), _p(k), B, Hq, Hkv, L, d, bq, bk, b, h, I0, I1, _p(ap)),
            "pool_scores_rows")
     return ap
@@ -186,12 +182,12 @@ def attn_sparse(q, k, v, row_ptr, col_idx, bq: int, bk: int) -> np.ndarray:
 
 
 def attn_sparse_rows(q, k, v, row_ptr, col_idx, bq: int, bk: int, b: int, h: int, I0: int, I1: int) -> np.ndarray:
-    """Eq. 3/4 for query blocks [I0, I1) of one (b, h) -> float64 [(I1-I0)*bq, d]."""
+    """Eq. 3/4 for query blocks [I0, I1) of one (b, h) -> float64 [(I1-I0)*bq, d] (rows past L stay zero)."""
     q, k, v = _f32(q), _f32(k), _f32(v)
     row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
     B, Hq, Hkv, L, d = _dims(q, k)
     cap = col_idx.shape[-1]
-    out = np.empty(((I1 - I0) * bq, d), dtype=np.float64)
+    out = np.zeros(((I1 - I0) * bq, d), dtype=np.float64)
     _check(_load().oracle_attn_sparse_rows(_p(q), _p(k), _p(v), B, Hq, Hkv, L, d, bq, bk, _p(row_ptr),
                                            _p(col_idx), cap, b, h, I0, I1, _p(out)), "attn_sparse_rows")
     return out

@@ -136,13 +136,15 @@ int oracle_attn_dense(const float* q, const float* k, const float* v, int B, int
 /* For each query block I (rows I*bq .. I*bq+bq-1) and key block J, the mean of
  * A over the bq x bk rectangle; A is the full-row softmax of Eq. 1. The loop is
  * Algorithm 1's: one query block at a time, never more than bq rows of A alive.
- * apool is [(I1 - I0), nkb] doubles.                                           */
+ * When L is not a multiple of a block size the last block of that axis is
+ * partial (nqb = ceil(L/bq), nkb = ceil(L/bk)) and its mean runs over the
+ * entries that exist. apool is [(I1 - I0), nkb] doubles.                        */
 int oracle_pool_scores_rows(const float* q, const float* k, int B, int Hq, int Hkv, int L, int d,
                             int bq, int bk, int b, int h, int I0, int I1, double* apool) {
   int rc = check_shape(B, Hq, Hkv, L, d);
   if (rc) return rc;
-  if (bq <= 0 || bk <= 0 || L % bq != 0 || L % bk != 0) return -4;
-  const int nqb = L / bq, nkb = L / bk;
+  if (bq <= 0 || bk <= 0) return -4;
+  const int nqb = (L + bq - 1) / bq, nkb = (L + bk - 1) / bk;
   if (b < 0 || b >= B || h < 0 || h >= Hq || I0 < 0 || I1 > nqb || I0 > I1) return -3;
   const int g = h / (Hq / Hkv);
   const float* khead = k + IDX4(b, g, 0, Hkv, L, d);
@@ -159,15 +161,19 @@ int oracle_pool_scores_rows(const float* q, const float* k, int B, int Hq, int H
       if (!p) continue;
       double* arow = apool + (size_t)(I - I0) * nkb;
       for (int J = 0; J < nkb; ++J) arow[J] = 0.0;
-      for (int r = 0; r < bq; ++r) {
+      const int rows = (I * bq + bq <= L) ? bq : L - I * bq; /* rows that exist in this query block */
+      for (int r = 0; r < rows; ++r) {
         probs_row(q + IDX4(b, h, I * bq + r, Hq, L, d), khead, L, d, p);
         for (int J = 0; J < nkb; ++J) {
           double s = 0.0;
-          for (int c = 0; c < bk; ++c) s += p[J * bk + c];
+          for (int c = 0; c < bk && J * bk + c < L; ++c) s += p[J * bk + c];
           arow[J] += s;
         }
       }
-      for (int J = 0; J < nkb; ++J) arow[J] /= (double)bq * (double)bk;
+      for (int J = 0; J < nkb; ++J) {
+        const int colsJ = (J * bk + bk <= L) ? bk : L - J * bk; /* keys that exist in this key block */
+        arow[J] /= (double)rows * (double)colsJ;
+      }
     }
     free(p);
   }
@@ -179,8 +185,8 @@ int oracle_pool_scores(const float* q, const float* k, int B, int Hq, int Hkv, i
                        int bk, double* apool) {
   int rc = check_shape(B, Hq, Hkv, L, d);
   if (rc) return rc;
-  if (bq <= 0 || bk <= 0 || L % bq != 0 || L % bk != 0) return -4;
-  const int nqb = L / bq, nkb = L / bk;
+  if (bq <= 0 || bk <= 0) return -4;
+  const int nqb = (L + bq - 1) / bq, nkb = (L + bk - 1) / bk;
   for (int b = 0; b < B; ++b)
     for (int h = 0; h < Hq; ++h) {
       rc = oracle_pool_scores_rows(q, k, B, Hq, Hkv, L, d, bq, bk, b, h, 0, nqb,
@@ -312,10 +318,10 @@ static int sparse_block(const float* q, const float* k, const float* v, int Hq, 
   const float* khead = k + IDX4(b, g, 0, Hkv, L, d);
   const float* vhead = v + IDX4(b, g, 0, Hkv, L, d);
   const double inv_sqrt_d = 1.0 / sqrt((double)d);
-  const int nkept = n_cols * bk;
+  const int nkept = n_cols * bk; /* slots; a key beyond L (partial last block) keeps its slot at -inf */
   double* s = (double*)malloc((size_t)(nkept > 0 ? nkept : 1) * sizeof(double));
   if (!s) return -9;
-  for (int r = 0; r < bq; ++r) {
+  for (int r = 0; r < bq && I * bq + r < L; ++r) {
     const float* qrow = q + IDX4(b, h, I * bq + r, Hq, L, d);
     double* o = out + (size_t)r * d;
     for (int c = 0; c < d; ++c) o[c] = 0.0;
@@ -324,6 +330,10 @@ static int sparse_block(const float* q, const float* k, const float* v, int Hq, 
     for (int t = 0; t < n_cols; ++t)
       for (int c = 0; c < bk; ++c) {
         const int j = cols[t] * bk + c;
+        if (j >= L) {
+          s[t * bk + c] = -INFINITY;
+          continue;
+        }
         const float* krow = khead + (size_t)j * d;
         double dot = 0.0;
         for (int e = 0; e < d; ++e) dot += (double)qrow[e] * (double)krow[e];
@@ -338,6 +348,7 @@ static int sparse_block(const float* q, const float* k, const float* v, int Hq, 
     for (int t = 0; t < n_cols; ++t)
       for (int c = 0; c < bk; ++c) {
         const int j = cols[t] * bk + c;
+        if (j >= L) continue;
         const double p = s[t * bk + c] / z;
         const float* vrow = vhead + (size_t)j * d;
         for (int e = 0; e < d; ++e) o[e] += p * (double)vrow[e];
@@ -355,8 +366,8 @@ int oracle_attn_sparse_rows(const float* q, const float* k, const float* v, int 
                             double* out) {
   int rc = check_shape(B, Hq, Hkv, L, d);
   if (rc) return rc;
-  if (bq <= 0 || bk <= 0 || L % bq != 0 || L % bk != 0) return -4;
-  const int nqb = L / bq, nkb = L / bk;
+  if (bq <= 0 || bk <= 0) return -4;
+  const int nqb = (L + bq - 1) / bq, nkb = (L + bk - 1) / bk;
   if (b < 0 || b >= B || h < 0 || h >= Hq || I0 < 0 || I1 > nqb || I0 > I1) return -3;
   const int32_t* rp = row_ptr + ((size_t)b * Hq + h) * (size_t)(nqb + 1);
   const int32_t* ci = col_idx + ((size_t)b * Hq + h) * (size_t)cap_per_head;
@@ -384,8 +395,8 @@ int oracle_attn_sparse(const float* q, const float* k, const float* v, int B, in
                        int cap_per_head, double* out) {
   int rc = check_shape(B, Hq, Hkv, L, d);
   if (rc) return rc;
-  if (bq <= 0 || bk <= 0 || L % bq != 0 || L % bk != 0) return -4;
-  const int nqb = L / bq;
+  if (bq <= 0 || bk <= 0) return -4;
+  const int nqb = (L + bq - 1) / bq;
   for (int b = 0; b < B; ++b)
     for (int h = 0; h < Hq; ++h) {
       rc = oracle_attn_sparse_rows(q, k, v, B, Hq, Hkv, L, d, bq, bk, row_ptr, col_idx, cap_per_head,
@@ -405,9 +416,9 @@ int oracle_attn_masked_bruteforce(const float* q, const float* k, const float* v
                                   const int32_t* col_idx, int cap_per_head, double* out) {
   int rc = check_shape(B, Hq, Hkv, L, d);
   if (rc) return rc;
-  if (bq <= 0 || bk <= 0 || L % bq != 0 || L % bk != 0) return -4;
+  if (bq <= 0 || bk <= 0) return -4;
   if ((size_t)L * (size_t)L > ((size_t)1 << 26)) return -6; /* tiny inputs only */
-  const int nqb = L / bq, nkb = L / bk;
+  const int nqb = (L + bq - 1) / bq, nkb = (L + bk - 1) / bk;
   double* M = (double*)malloc((size_t)L * L * sizeof(double));
   double* S = (double*)malloc((size_t)L * L * sizeof(double));
   if (!M || !S) {

@@ -29,12 +29,19 @@ MUTANTS = [
      "        for (int c = 0; c < d; ++c) o[c] += p[j] * (double)(khead + (size_t)j * d)[c];\n      }\n    }\n    free(p);",
      [lambda: pins.test_dense_zero_queries_give_mean_of_values()]),
     ("pooling: divided by bq only",
-     "arow[J] /= (double)bq * (double)bk;", "arow[J] /= (double)bq;",
+     "arow[J] /= (double)rows * (double)colsJ;", "arow[J] /= (double)rows;",
      [lambda: pins.test_pool_uniform_when_queries_are_zero()]),
     ("pooling: query rows indexed with the key block size",
      "probs_row(q + IDX4(b, h, I * bq + r, Hq, L, d), khead, L, d, p);",
      "probs_row(q + IDX4(b, h, I * bk + r, Hq, L, d), khead, L, d, p);",
      [lambda: pins.test_pool_matches_reshape_mean_of_torch_probs(16, 8)]),
+    ("pooling: a partial last block is divided by the full block area",
+     "arow[J] /= (double)rows * (double)colsJ;", "arow[J] /= (double)bq * (double)bk;",
+     [lambda: pins.test_ragged_pool_matches_ceil_mode_average_pooling()]),
+    ("sparse: keys past the end of a partial last block are not masked",
+     "        if (j >= L) {\n          s[t * bk + c] = -INFINITY;\n          continue;\n        }",
+     "        if (j >= L) {\n          s[t * bk + c] = 0.0;\n          continue;\n        }",
+     [lambda: pins.test_ragged_sparse_matches_bruteforce_and_dense()]),
     ("count rule: floor instead of guarded ceil",
      "int kk = (int)ceil(rho * (double)n - 1e-9);", "int kk = (int)floor(rho * (double)n);",
      [lambda: pins.test_kept_blocks_rule()]),
@@ -47,8 +54,8 @@ MUTANTS = [
      "      if (best < 0 || arow[J] < arow[best]) best = J;",
      [lambda: pins.test_select_maximises_kept_mass_by_exhaustive_search()]),
     ("sparse: key offset uses the query block size",
-     "        const int j = cols[t] * bk + c;\n        const float* krow = khead + (size_t)j * d;",
-     "        const int j = cols[t] * bq + c;\n        const float* krow = khead + (size_t)j * d;",
+     "        const int j = cols[t] * bk + c;\n        if (j >= L) {",
+     "        const int j = cols[t] * bq + c;\n        if (j >= L) {",
      [lambda: pins.test_sparse_matches_bruteforce_mask_sdpa_and_renormalised_dense(16, 8, 2)]),
     ("sparse: normalised by the number of kept keys instead of the softmax sum",
      "        const double p = s[t * bk + c] / z;\n        const float* vrow = vhead + (size_t)j * d;",

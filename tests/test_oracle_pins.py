@@ -306,6 +306,63 @@ def test_sparse_rows_ragged_csr_and_empty_row():
 
 
 # ----------------------------------------------------------------------------- closed form W1
+# ----------------------------------------------------------------------------- ragged L (partial last blocks)
+def test_ragged_pool_matches_ceil_mode_average_pooling():
+    """Library special case: torch's avg_pool2d with ceil_mode=True averages a window that hangs over
+    the edge over the entries that exist."""
+    L, bq, bk = 45, 16, 8
+    q, k, _ = _rand(1, 2, 2, L, 8, seed=31)
+    P = torch.softmax(q.double() @ k.double().transpose(-1, -2) / math.sqrt(8), dim=-1)
+    want = torch.nn.functional.avg_pool2d(P, kernel_size=(bq, bk), stride=(bq, bk), ceil_mode=True)
+    got = oracle.pool_scores(q, k, bq, bk)
+    assert got.shape == (1, 2, 3, 6)
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-15)
+    # the row-range entry point gives the same numbers
+    np.testing.assert_allclose(got[0, 1, :2], oracle.pool_scores_rows(q, k, bq, bk, 0, 1, 0, 2), rtol=0, atol=0)
+    # each row of a full query block still sums to sum over key blocks of (mass / area): check total mass instead
+    area = np.array([bk] * 5 + [L - 5 * bk], dtype=np.float64)
+    rows = np.array([bq, bq, L - 2 * bq], dtype=np.float64)
+    mass = (got * area[None, None, None, :] * rows[None, None, :, None]).sum(-1)
+    np.testing.assert_allclose(mass, np.broadcast_to(rows, mass.shape), rtol=1e-12)
+
+
+def test_ragged_sparse_matches_bruteforce_and_dense():
+    L, bq, bk, d = 45, 16, 8, 8
+    q, k, v = _rand(1, 2, 1, L, d, seed=32)
+    nqb, nkb = 3, 6
+    # every block listed: equals dense attention over the 45 real keys
+    rp = np.tile(np.arange(nqb + 1, dtype=np.int32) * nkb, (1, 2, 1))
+    ci = np.tile(np.arange(nkb, dtype=np.int32), (1, 2, nqb))
+    np.testing.assert_allclose(oracle.attn_sparse(q, k, v, rp, ci, bq, bk), oracle.attn_dense(q, k, v), rtol=1e-12, atol=1e-14)
+    # a pattern that keeps the partial last key block plus one other, against the explicit L x L mask and against
+    # torch SDPA with the boolean mask built from first principles
+    rp = np.tile(np.arange(nqb + 1, dtype=np.int32) * 2, (1, 2, 1))
+    ci = np.tile(np.array([1, 5, 0, 5, 3, 5], dtype=np.int32), (1, 2, 1))
+    got = oracle.attn_sparse(q, k, v, rp, ci, bq, bk)
+    np.testing.assert_allclose(got, oracle.attn_masked_bruteforce(q, k, v, rp, ci, bq, bk), rtol=1e-12, atol=1e-14)
+    keep = np.zeros((L, L), dtype=bool)
+    for i in range(L):
+        for j in range(L):
+            keep[i, j] = (j // bk) in ci[0, 0, 2 * (i // bq): 2 * (i // bq) + 2]
+    want = torch.nn.functional.scaled_dot_product_attention(q.double(), k.double().repeat_interleave(2, 1), v.double().repeat_interleave(2, 1),
+                                                            attn_mask=torch.from_numpy(keep))
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-11, atol=1e-13)
+    # rows-variant: the rows past L of the last (partial) query block stay zero
+    last = oracle.attn_sparse_rows(q, k, v, rp, ci, bq, bk, 0, 1, 2, 3)
+    assert last.shape == (bq, d) and (last[L - 2 * bq:] == 0).all()
+    np.testing.assert_allclose(last[:L - 2 * bq], got[0, 1, 2 * bq:], rtol=0, atol=0)
+
+
+def test_ragged_selection_counts_blocks_with_ceil():
+    L, bq, bk = 45, 16, 8
+    q, k, _ = _rand(1, 1, 1, L, 8, seed=33)
+    rp, ci, ap, _ = oracle.select_pattern(q, k, bq, bk, 0.5)
+    assert ap.shape[-2:] == (3, 6) and oracle.kept_blocks(0.5, 6) == 3
+    assert rp.tolist() == [[[0, 3, 6, 9]]] and ci.shape[-1] == 9
+    for I in range(3):
+        assert set(ci[0, 0, 3 * I: 3 * I + 3]) == set(np.argsort(-ap[0, 0, I], kind="stable")[:3])
+
+
 def test_closed_form_w1():
     g = _read_golden("w1_closed_form.txt")
     L = 4
