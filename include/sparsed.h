@@ -25,9 +25,11 @@
  *    span less than 2^31 bytes.
  *  - Grouped-query attention: q has Hq heads, k and v have Hkv heads with
  *    Hq % Hkv == 0; query head h reads key/value head h / (Hq / Hkv).
- *  - Supported shapes: D in {64, 128}; L a multiple of 64 (bf16) or 32 (fp32);
- *    block_q in {32, 64, 128}; block_k == 64 for bf16, block_k in {32, 64} for
- *    fp32; L a multiple of block_q and block_k where blocks are involved.
+ *  - Supported shapes: D in {64, 128}; any L >= 1; block_q in {32, 64, 128};
+ *    block_k == 64 for bf16, block_k in {32, 64} for fp32. L need not be a
+ *    multiple of the block sizes: there are nqb = ceil(L / block_q) query blocks
+ *    and nkb = ceil(L / block_k) key blocks, the last of each possibly partial
+ *    (the paper pools with L // block_size and is silent on a remainder).
  *  - Arithmetic: bf16 tensors are multiplied on the bf16 matrix cores with
  *    fp32 accumulation, softmax in fp32, probabilities rounded to bf16 before
  *    the product with V. fp32 tensors use fp32 matrix cores throughout.
@@ -108,7 +110,8 @@ sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor*
  * Pattern selection at the switch step (Section 3.3 "Isolated Selection" with a
  * single key range, Eq. 6; Algorithm 1, the per-query-block loop):
  *   1. A' = average of the softmax probabilities A of Eq. 1 over each
- *      block_q x block_k rectangle (each row of A normalised over all L keys);
+ *      block_q x block_k rectangle (each row of A normalised over all L keys;
+ *      a partial last block is averaged over the entries that exist);
  *   2. for every query block keep the k = sparsed_kept_blocks(rho, nkb) key
  *      blocks with the largest A' (ties: lower block index), listed ascending.
  * The L x L matrix A is never formed. Fills out_block_index->row_ptr / col_idx
@@ -127,7 +130,8 @@ sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_ten
 /*
  * Sparse attention of the later steps ("Sparse Reusing"; Eq. 3 with the mask of
  * Eq. 4): rows of query block I attend only to the keys of the key blocks
- * listed for I; the softmax is normalised over those keys only. The index
+ * listed for I (those below L, for a partial last block); the softmax is
+ * normalised over those keys only. The index
  * contents are trusted (check them with sparsed_index_validate); its shape
  * fields are checked against q.
  */
@@ -157,7 +161,7 @@ sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sp
  * taken symmetric because attention here is bidirectional), plus the key blocks
  * that overlap the first sink_tokens keys. The same rows for every head; rows
  * have different lengths. idx->B, H, nqb, nkb, block_q, block_k must describe a
- * sequence of seq_len tokens; cap_per_head must be >=
+ * sequence of seq_len tokens (block counts rounded up); cap_per_head must be >=
  * sparsed_index_window_entries(...), else SPARSED_ERR_INDEX.
  */
 sparsed_status sparsed_index_fill_window(sparsed_block_index* idx, int32_t seq_len, int32_t window_tokens,

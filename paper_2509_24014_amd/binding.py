@@ -187,9 +187,7 @@ def attn_dense(q, k, v, out: Optional[torch.Tensor] = None, lse_out: Optional[to
 def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pooled_out, index, stream):
     lib = load_library()
     B, H, L, D = q.shape
-    if L % block_q or L % block_k:
-        raise SparsedError(2, f"L {L} is not a multiple of block_q {block_q} and block_k {block_k}")
-    nqb, nkb = L // block_q, L // block_k
+    nqb, nkb = -(-L // block_q), -(-L // block_k)
     if prefill_blocks is None:
         keep = kept_blocks(rho, nkb)
     else:
@@ -260,8 +258,8 @@ def index_fill_window(B: int, H: int, seq_len: int, block_q: int, block_k: int, 
     cap = index_window_entries(seq_len, block_q, block_k, window_tokens, sink_tokens)
     if cap < 0:
         raise SparsedError(5, "bad window pattern arguments")
-    index = BlockIndex(torch.empty(B, H, seq_len // block_q + 1, dtype=torch.int32, device=device),
-                       torch.empty(B, H, max(cap, 1), dtype=torch.int32, device=device), block_q, block_k, seq_len // block_k)
+    index = BlockIndex(torch.empty(B, H, -(-seq_len // block_q) + 1, dtype=torch.int32, device=device),
+                       torch.empty(B, H, max(cap, 1), dtype=torch.int32, device=device), block_q, block_k, -(-seq_len // block_k))
     ex = _Exec(_stream_ptr(stream), None, 0, None, None, None)
     ci = index._c()
     _check(lib.sparsed_index_fill_window(ctypes.byref(ci), seq_len, window_tokens, sink_tokens, ctypes.byref(ex)))

@@ -72,22 +72,16 @@ sparsed_status check_blocks(const sparsed_tensor* q, int bq, int bk) {
   if (bq != 32 && bq != 64 && bq != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_q %d not in {32,64,128}", bq);
   if (q->dtype == SPARSED_BF16 && bk != 64) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d: bf16 supports 64", bk);
   if (q->dtype == SPARSED_F32 && bk != 32 && bk != 64) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64}", bk);
-  if (q->L % bq || q->L % bk) return fail(SPARSED_ERR_SHAPE, "L %d is not a multiple of block_q %d and block_k %d", q->L, bq, bk);
   return SPARSED_OK;
 }
 
-sparsed_status check_len(const sparsed_tensor* q) {
-  const int m = q->dtype == SPARSED_BF16 ? 64 : 32;
-  if (q->L % m) return fail(SPARSED_ERR_SHAPE, "L %d is not a multiple of %d", q->L, m);
-  return SPARSED_OK;
-}
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 sparsed_status check_index_shape(const sparsed_block_index* ix, const sparsed_tensor* q) {
   if (!ix) return fail(SPARSED_ERR_NULL, "block index is NULL");
   if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
   if (ix->block_q <= 0 || ix->block_k <= 0) return fail(SPARSED_ERR_INDEX, "block index has non-positive block sizes");
-  if (ix->B != q->B || ix->H != q->H || ix->nqb != q->L / ix->block_q || ix->nkb != q->L / ix->block_k ||
-      q->L % ix->block_q || q->L % ix->block_k)
+  if (ix->B != q->B || ix->H != q->H || ix->nqb != ceil_div(q->L, ix->block_q) || ix->nkb != ceil_div(q->L, ix->block_k))
     return fail(SPARSED_ERR_INDEX, "block index [B=%d,H=%d,nqb=%d,nkb=%d,%dx%d] does not describe q [%d,%d,%d,%d]", ix->B, ix->H,
                 ix->nqb, ix->nkb, ix->block_q, ix->block_k, q->B, q->H, q->L, q->D);
   if (ix->cap_per_head < 0) return fail(SPARSED_ERR_INDEX, "negative cap_per_head");
@@ -136,7 +130,6 @@ sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tenso
     return st;
   if ((st = check_qk(q, k, "k")) || (st = check_qk(q, v, "v")) || (st = check_out(q, out))) return st;
   if (k->H != v->H) return fail(SPARSED_ERR_SHAPE, "k has %d heads, v has %d", k->H, v->H);
-  if ((st = check_len(q))) return st;
   AttnArgs a{};
   a.q = targ(q);
   a.k = targ(k);
@@ -172,7 +165,7 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
                            int32_t prefill_blocks, bool isolated, sparsed_block_index* ix, const sparsed_exec* ex) {
   sparsed_status st;
   if ((st = check_tensor(q, "q")) || (st = check_tensor(k, "k")) || (st = check_qk(q, k, "k"))) return st;
-  if ((st = check_len(q)) || (st = check_blocks(q, bq, bk))) return st;
+  if ((st = check_blocks(q, bq, bk))) return st;
   if (!(rho > 0.0) || !(rho <= 1.0)) return fail(SPARSED_ERR_RANGE, "rho %g outside (0, 1]", rho);
   if ((st = check_index_shape(ix, q))) return st;
   if (ix->block_q != bq || ix->block_k != bk) return fail(SPARSED_ERR_INDEX, "block index blocks %dx%d differ from %dx%d", ix->block_q, ix->block_k, bq, bk);
@@ -238,7 +231,6 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   p.nkb = nkb;
   p.block_k = bk;
   p.scale_log2 = scale_log2(q->D);
-  p.inv_area = 1.0f / ((float)bq * (float)bk);
   hipError_t e = bf16 ? launch_pool_bf16(q->D, bq, p, s) : launch_pool_f32(q->D, bq, p, s);
   if (e != hipSuccess) return hip_fail(e, "pooled-score launch");
   // 3. per-row top-k into the CSR index
@@ -302,8 +294,7 @@ int32_t sparsed_n_dense_steps(int32_t T, double skip) {
 
 size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
   if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
-  if (q->L % block_q || q->L % block_k) return 0;
-  return select_ws_bytes(q->B, q->H, q->L, q->L / block_q, q->L / block_k);
+  return select_ws_bytes(q->B, q->H, q->L, ceil_div(q->L, block_q), ceil_div(q->L, block_k));
 }
 
 sparsed_status sparsed_index_validate(const sparsed_block_index* ix, const sparsed_exec* ex) {
@@ -333,8 +324,8 @@ sparsed_status sparsed_index_fill_window(sparsed_block_index* ix, int32_t seq_le
                                          const sparsed_exec* ex) {
   if (!ix) return fail(SPARSED_ERR_NULL, "block index is NULL");
   if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
-  if (ix->B <= 0 || ix->H <= 0 || ix->block_q <= 0 || ix->block_k <= 0 || seq_len <= 0 || seq_len % ix->block_q ||
-      seq_len % ix->block_k || ix->nqb != seq_len / ix->block_q || ix->nkb != seq_len / ix->block_k)
+  if (ix->B <= 0 || ix->H <= 0 || ix->block_q <= 0 || ix->block_k <= 0 || seq_len <= 0 ||
+      ix->nqb != ceil_div(seq_len, ix->block_q) || ix->nkb != ceil_div(seq_len, ix->block_k))
     return fail(SPARSED_ERR_INDEX, "block index does not describe a sequence of %d tokens", seq_len);
   if (window_tokens < 0 || sink_tokens < 0) return fail(SPARSED_ERR_RANGE, "negative window or sink length");
   WindowArgs a{};
@@ -362,10 +353,10 @@ sparsed_status sparsed_index_fill_window(sparsed_block_index* ix, int32_t seq_le
 }
 
 int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t block_k, int32_t window_tokens, int32_t sink_tokens) {
-  if (seq_len <= 0 || block_q <= 0 || block_k <= 0 || seq_len % block_q || seq_len % block_k || window_tokens < 0 || sink_tokens < 0) return -1;
+  if (seq_len <= 0 || block_q <= 0 || block_k <= 0 || window_tokens < 0 || sink_tokens < 0) return -1;
   const int sink_blocks = (sink_tokens + block_k - 1) / block_k;
   int64_t total = 0;
-  for (int I = 0; I < seq_len / block_q; ++I) {
+  for (int I = 0; I < ceil_div(seq_len, block_q); ++I) {
     int first, last;
     window_block_range(I, block_q, block_k, seq_len, window_tokens / 2, &first, &last);
     total += (sink_blocks < first ? sink_blocks : first) + (last - first + 1);

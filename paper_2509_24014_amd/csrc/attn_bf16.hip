@@ -63,11 +63,16 @@ __global__ __launch_bounds__(NW * 64)
     n = end - beg;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
-    n = a.L / kTileK;
+    n = (a.L + kTileK - 1) / kTileK;
   }
+  // A sequence length that is not a multiple of the tile leaves the last key block partial: its
+  // missing keys are masked to -inf in the softmax and its missing rows never fetched.
+  const int last_blk = (a.L - 1) / kTileK;
+  const int tail_keys = a.L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
+  auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
   QFrag<D, NQ> qf;
-  qf.load(qbase + (int64_t)row0 * a.q.sl, a.q.sl, lane);
+  qf.load(qbase, row0, a.L, a.q.sl, lane);
 
   float M[NQ], lsum[NQ];
   f32x16 o[NQ][D / 32];
@@ -111,15 +116,34 @@ __global__ __launch_bounds__(NW * 64)
   const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2), v_tile_bytes = (int32_t)(kTileK * a.v.sl * 2);
   auto copy_k = [&](int blk, char* dst) { kdma.issue(krsrc, uni(blk) * k_tile_bytes, dst, wave); };
   auto copy_v = [&](int blk, char* dst) { vdma.issue(vrsrc, uni(blk) * v_tile_bytes, dst, wave); };
+  // the same for a tile that may be the partial last block (prologue and the last few tiles only)
+  auto copy_k_any = [&](int blk, char* dst) {
+    const int ub = uni(blk);
+    if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
+    else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
+  };
+  auto copy_v_any = [&](int blk, char* dst) {
+    const int ub = uni(blk);
+    if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
+    else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
+  };
 
   const float c = a.scale_log2;
 
   // Online softmax of one 32-key sub-tile: s (fp32 logits) -> p (bf16), updates M / lsum, reports the
   // factor by which the output accumulator has to be rescaled (1 unless the reference maximum moved).
-  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise) {
+  // `valid`: keys of this sub-tile that exist (32 or more = all; only the partial last block has fewer).
+  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise, int valid) {
     any_raise = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
+      if (valid < 32) {
+        // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the sub-tile
+        const int mine = valid - 8 * g;
+#pragma unroll
+        for (int x = 0; x < 16; ++x)
+          if (16 * (x >> 3) + (x & 7) >= mine) s[nq][x] = -__builtin_inff();
+      }
       float mx = fmaxf(s[nq][0], s[nq][1]);
 #pragma unroll
       for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][x]), s[nq][x + 1]);
@@ -181,21 +205,28 @@ __global__ __launch_bounds__(NW * 64)
     char* const vb_free = (P) ? vbuf0 : vbuf1;                                                     \
     const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
     const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
-    if (has_k2) copy_k(blk2, kb_free);                                                             \
-    if (kHasV && has_next) copy_v(blk1, vb_free);                                                  \
+    if (STEADY) {                                                                                  \
+      copy_k(blk2, kb_free);                                                                       \
+      if (kHasV) copy_v(blk1, vb_free);                                                            \
+    } else {                                                                                       \
+      if (has_k2) copy_k_any(blk2, kb_free);                                                       \
+      if (kHasV && has_next) copy_v_any(blk1, vb_free);                                            \
+    }                                                                                              \
+    const int valid_odd = (STEADY) ? 32 : keys_of(uni(blk0)) - 32;                                 \
+    const int valid_even = (STEADY) ? 32 : keys_of(uni(blk1));                                     \
     const int blk_new = col_at((T) + 4);                                                           \
     float alpha[NQ];                                                                               \
     bool any_raise;                                                                                \
     if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                     \
     if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 0, vaddr, p_even, o);                             \
-    softmax_sub(s_odd, p_odd, alpha, any_raise);                                                   \
+    softmax_sub(s_odd, p_odd, alpha, any_raise, valid_odd);                                        \
     if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                          \
     if (kHasV && any_raise) rescale_output(alpha);                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                             \
     if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                      \
     if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 1, vaddr, p_odd, o);                              \
     if (has_next) {                                                                                \
-      softmax_sub(s_even, p_even, alpha, any_raise);                                               \
+      softmax_sub(s_even, p_even, alpha, any_raise, valid_even);                                   \
       if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                        \
       if (kHasV && any_raise) rescale_output(alpha);                                               \
     }                                                                                              \
@@ -208,21 +239,23 @@ __global__ __launch_bounds__(NW * 64)
 
   if (n > 0) {
     // prologue: K(0), K(1), V(0) into LDS; S(0); then sub-step 0: S(1) alongside softmax(0)
-    copy_k(blk0, kbuf0);
-    if (n > 1) copy_k(blk1, kbuf1);
-    if (kHasV) copy_v(blk0, vbuf0);
+    copy_k_any(blk0, kbuf0);
+    if (n > 1) copy_k_any(blk1, kbuf1);
+    if (kHasV) copy_v_any(blk0, vbuf0);
     __syncthreads();
     logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
     logits_sub<D, NQ, true>(kbuf0, 1, kaddr, qf, s_odd);
     {
       float alpha[NQ];
       bool any_raise;
-      softmax_sub(s_even, p_even, alpha, any_raise);  // O is still zero: nothing to rescale
+      softmax_sub(s_even, p_even, alpha, any_raise, keys_of(uni(blk0)));  // O is still zero: nothing to rescale
     }
     __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
+    // the steady loop never touches the partial last block: one more tile is left to the tail loop
+    const int steady_reach = 3 + (tail_keys < kTileK ? 1 : 0);
     int t = 0;
-    while (t + 3 < n) {
+    while (t + steady_reach < n) {
       SPARSED_TILE_STEP(0, true, t);
       SPARSED_TILE_STEP(1, true, t + 1);
       t += 2;
@@ -242,6 +275,7 @@ __global__ __launch_bounds__(NW * 64)
   for (int nq = 0; nq < NQ; ++nq) {
     const float ltot = pair_sum(lsum[nq]);
     const int row = row0 + nq * 32 + j;
+    if (row >= a.L) continue;  // partial last query tile
     if (a.lse != nullptr && g == 0)
       a.lse[(int64_t)bh * a.L + row] = (M[nq] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
     if (kHasV) {
@@ -264,10 +298,11 @@ __global__ __launch_bounds__(NW * 64)
 }
 
 int dense_qtile_bf16(int L) {
-  if (L <= 0 || L % 64 != 0) return 0;
+  if (L <= 0) return 0;
   if (L % 256 == 0) return 256;
   if (L % 128 == 0) return 128;
-  return 64;
+  if (L % 64 == 0) return 64;
+  return L >= 1024 ? 256 : L >= 256 ? 128 : 64;  // partial last tile: waste at most one tile of rows
 }
 
 template <int D, int NQ, int NW, Mode MODE>
@@ -292,8 +327,8 @@ static hipError_t launch_by_qtile(int qtile, const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bf16(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s) {
   const int qtile = (mode == Mode::kSparse) ? block_q : dense_qtile_bf16(a.L);
-  if (qtile == 0 || a.L % qtile != 0) return hipErrorInvalidValue;
-  a.n_qtiles = a.L / qtile;
+  if (qtile == 0) return hipErrorInvalidValue;
+  a.n_qtiles = (a.L + qtile - 1) / qtile;
   if (D == 128) {
     if (mode == Mode::kDense) return launch_by_qtile<128, Mode::kDense>(qtile, a, s);
     if (mode == Mode::kSparse) return launch_by_qtile<128, Mode::kSparse>(qtile, a, s);

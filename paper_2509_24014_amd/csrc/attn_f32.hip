@@ -41,11 +41,11 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
     n_tiles = (end - beg) * tiles_per_block;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
-    n_tiles = a.L / kTileKF;
+    n_tiles = (a.L + kTileKF - 1) / kTileKF;
   }
 
   QFragF32<D> qf;
-  qf.load(qbase + (int64_t)row0 * a.q.sl, a.q.sl, lane);
+  qf.load(qbase, row0, a.L, a.q.sl, lane);
 
   float M = -1e30f, lsum = 0.f;
   f32x16 o[D / 32];
@@ -63,12 +63,21 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
     } else {
       key0 = t * kTileKF;
     }
+    // keys of this tile that exist: fewer than 32 only at the end of a sequence whose length is not a
+    // multiple of the tile; a tile wholly past the end (second half of a partial 64-key block) is skipped
+    const int valid = a.L - key0 < kTileKF ? a.L - key0 : kTileKF;
+    if (valid <= 0) continue;  // uniform over the work-group
     __syncthreads();  // everyone is done reading the previous tile
-    T::template stage<NT>(kbase + (int64_t)key0 * a.k.sl, a.k.sl, klds, T::kKStride, tid);
-    if (kHasV) T::template stage<NT>(vbase + (int64_t)key0 * a.v.sl, a.v.sl, vlds, D, tid);
+    T::template stage<NT>(kbase + (int64_t)key0 * a.k.sl, a.k.sl, klds, T::kKStride, tid, valid);
+    if (kHasV) T::template stage<NT>(vbase + (int64_t)key0 * a.v.sl, a.v.sl, vlds, D, tid, valid);
     __syncthreads();
 
     f32x16 s = logits_tile_f32<D>(klds, qf, lane);
+    if (valid < kTileKF) {
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        if (8 * (x / 4) + 4 * g + (x % 4) >= valid) s[x] = -__builtin_inff();
+    }
 
     float mx = s[0];
 #pragma unroll
@@ -101,6 +110,7 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
 
   const float ltot = lsum + other_half_f(lsum);
   const int row = row0 + j;
+  if (row >= a.L) return;  // partial last query tile
   if (a.lse != nullptr && g == 0) a.lse[(int64_t)bh * a.L + row] = (M + log2f(ltot)) * 0.6931471805599453f;
   if (kHasV) {
     const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
@@ -118,10 +128,11 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
 }
 
 int dense_qtile_f32(int L) {
-  if (L <= 0 || L % 32 != 0) return 0;
+  if (L <= 0) return 0;
   if (L % 128 == 0) return 128;
   if (L % 64 == 0) return 64;
-  return 32;
+  if (L % 32 == 0) return 32;
+  return L >= 256 ? 128 : L >= 64 ? 64 : 32;  // partial last tile
 }
 
 template <int D, int NW, Mode MODE>
@@ -144,8 +155,8 @@ static hipError_t launch_by_qtile_f32(int qtile, const AttnArgs& a, hipStream_t 
 
 hipError_t launch_attn_f32(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s) {
   const int qtile = (mode == Mode::kSparse) ? block_q : dense_qtile_f32(a.L);
-  if (qtile == 0 || a.L % qtile != 0) return hipErrorInvalidValue;
-  a.n_qtiles = a.L / qtile;
+  if (qtile == 0) return hipErrorInvalidValue;
+  a.n_qtiles = (a.L + qtile - 1) / qtile;
   if (D == 128) {
     if (mode == Mode::kDense) return launch_by_qtile_f32<128, Mode::kDense>(qtile, a, s);
     if (mode == Mode::kSparse) return launch_by_qtile_f32<128, Mode::kSparse>(qtile, a, s);

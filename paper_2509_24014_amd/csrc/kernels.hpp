@@ -34,7 +34,6 @@ struct PoolArgs {
   int32_t B, Hq, Hkv, L;
   int32_t nqb, nkb, block_k;
   float scale_log2;        // log2(e) / sqrt(D)
-  float inv_area;          // 1 / (block_q * block_k)
 };
 
 // Arguments of the per-row top-k kernel (Eq. 6): one wavefront per pooled row.

@@ -54,9 +54,14 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFrag<D, 1> qf;
-  qf.load(qbase + (int64_t)row0 * a.q.sl, a.q.sl, lane);
-  const float lse2 = a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f;
+  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
+  const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.nkb;
+  const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
+  const int last_blk = (a.L - 1) / kTileK;
+  const int tail_keys = a.L - last_blk * kTileK;  // keys that exist in the last key block
+  auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
   TileDma<D, NT, false> kdma;
   kdma.init(a.k.sl, wave, lane);
@@ -67,9 +72,20 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int n = a.nkb;
   const float c = a.scale_log2;
 
+  auto copy_k_any = [&](int blk, char* dst) {  // a tile that may be the partial last block
+    if (blk == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, blk * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
+    else kdma.issue(krsrc, blk * k_tile_bytes, dst, wave);
+  };
   f32x16 s_even[1], s_odd[1];
   float carry = 0.f;  // per-lane sum of the even sub-tile of the key block in progress
-  auto expsum_sub = [&](f32x16(&s)[1]) -> float {
+  const int g = lane >> 5;
+  auto expsum_sub = [&](f32x16(&s)[1], int valid) -> float {  // valid: keys of the sub-tile that exist (>= 32: all)
+    if (valid < 32) {
+      const int mine = valid - 8 * g;  // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        if (16 * (x >> 3) + (x & 7) >= mine) s[0][x] = -__builtin_inff();
+    }
     float part = 0.f;
 #pragma unroll
     for (int x = 0; x < 16; ++x) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][x], c, -lse2));
@@ -82,7 +98,7 @@ void pool_bf16_kernel(const PoolArgs a) {
       float tot = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) tot += wsum[t & 1][w];
-      arow[t] = tot * a.inv_area;
+      arow[t] = tot * (1.0f / (float)(rows_here * keys_of(t)));  // mean over the entries that exist
     }
   };
 
@@ -94,16 +110,17 @@ void pool_bf16_kernel(const PoolArgs a) {
     char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
     const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
     const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
-    if (has_k2) kdma.issue(krsrc, ((T) + 2) * k_tile_bytes, kb_free, wave);                        \
+    if (STEADY) kdma.issue(krsrc, ((T) + 2) * k_tile_bytes, kb_free, wave);                        \
+    else if (has_k2) copy_k_any((T) + 2, kb_free);                                                 \
     if (has_next) logits_sub<D, 1, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                      \
-    float part = carry + expsum_sub(s_odd);                                                        \
+    float part = carry + expsum_sub(s_odd, (STEADY) ? 32 : keys_of(T) - 32);                       \
     if (STEADY) sched_substep_interleave<D, 1, false>();                                           \
     part = wave_sum_to_last_lane(part);                                                            \
     if (lane == 63) wsum[(P)][wave] = part;                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                             \
     if (has_next) {                                                                                \
       logits_sub<D, 1, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                                   \
-      carry = expsum_sub(s_even);                                                                  \
+      carry = expsum_sub(s_even, (STEADY) ? 32 : keys_of((T) + 1));                                \
       if (STEADY) sched_substep_interleave<D, 1, false>();                                         \
     }                                                                                              \
     __syncthreads();                                                                               \
@@ -111,16 +128,17 @@ void pool_bf16_kernel(const PoolArgs a) {
   }
 
   // prologue: K(0), K(1) into LDS; S(0); then sub-step 0: S(1) alongside the sums of sub-tile 0
-  kdma.issue(krsrc, 0, kbuf0, wave);
-  if (n > 1) kdma.issue(krsrc, k_tile_bytes, kbuf1, wave);
+  copy_k_any(0, kbuf0);
+  if (n > 1) copy_k_any(1, kbuf1);
   __syncthreads();
   logits_sub<D, 1, true>(kbuf0, 0, kaddr, qf, s_even);
   logits_sub<D, 1, true>(kbuf0, 1, kaddr, qf, s_odd);
-  carry = expsum_sub(s_even);
+  carry = expsum_sub(s_even, keys_of(0));
   __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
+  const int steady_reach = 3 + (tail_keys < kTileK ? 1 : 0);  // the steady loop never touches a partial last block
   int t = 0;
-  while (t + 3 < n) {
+  while (t + steady_reach < n) {
     SPARSED_POOL_STEP(0, true, t);
     SPARSED_POOL_STEP(1, true, t + 1);
     t += 2;
@@ -157,19 +175,28 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFragF32<D> qf;
-  qf.load(qbase + (int64_t)row0 * a.q.sl, a.q.sl, lane);
-  const float lse2 = a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f;
+  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
+  const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.nkb;
+  const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
+  const int g = lane >> 5;
 
   const int tiles_per_block = a.block_k / kTileKF;
-  const int n_tiles = a.L / kTileKF;
+  const int n_tiles = (a.L + kTileKF - 1) / kTileKF;
   const float c = a.scale_log2;
   float acc = 0.f;  // thread 0: running sum of the current key block
   for (int t = 0; t < n_tiles; ++t) {
+    const int valid = a.L - t * kTileKF < kTileKF ? a.L - t * kTileKF : kTileKF;  // keys of this tile that exist (>= 1)
     __syncthreads();
-    T::template stage<NT>(kbase + (int64_t)t * kTileKF * a.k.sl, a.k.sl, klds, T::kKStride, tid);
+    T::template stage<NT>(kbase + (int64_t)t * kTileKF * a.k.sl, a.k.sl, klds, T::kKStride, tid, valid);
     __syncthreads();
     f32x16 s = logits_tile_f32<D>(klds, qf, lane);
+    if (valid < kTileKF) {
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        if (8 * (x / 4) + 4 * g + (x % 4) >= valid) s[x] = -__builtin_inff();
+    }
     float part = 0.f;
 #pragma unroll
     for (int x = 0; x < 16; ++x) part += exp2f(__builtin_fmaf(s[x], c, -lse2));
@@ -179,8 +206,10 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
     if (tid == 0) {
 #pragma unroll
       for (int w = 0; w < NW; ++w) acc += wsum[w];
-      if ((t + 1) % tiles_per_block == 0) {
-        arow[t / tiles_per_block] = acc * a.inv_area;
+      if ((t + 1) % tiles_per_block == 0 || t == n_tiles - 1) {  // key block complete (the last one may be partial)
+        const int J = t / tiles_per_block;
+        const int keys_here = a.L - J * a.block_k < a.block_k ? a.L - J * a.block_k : a.block_k;
+        arow[J] = acc * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
         acc = 0.f;
       }
     }

@@ -14,7 +14,7 @@
 // whose A operand is 8 consecutive keys of one column d of V. The output accumulator again has
 // one query per lane.
 //
-// Data path. K and V tiles go global -> LDS directly (global_load_lds_dwordx4: lane i of a wave
+// Data path. K and V tiles go global -> LDS directly (buffer_load_dwordx4 ... lds: lane i of a wave
 // deposits its 16 bytes at LDS base + 16*i); the LDS layouts below are realised on the GLOBAL side
 // (each lane fetches the chunk that belongs in its LDS slot). K fragments are 16-byte LDS reads. V fragments use the LDS
 // transpose read ds_read_b64_tr_b16: within a block of 16 lanes, result lane L gets element (L%4)
@@ -121,19 +121,38 @@ struct TileDma {
   __device__ __forceinline__ void init(int64_t stride_l, int wave_in_group, int lane) {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
+      int row, chunk;
+      source_of(wave_in_group * kPerWave + u, lane, &row, &chunk);
+      goff[u] = (int32_t)(row * stride_l * 2 + chunk * 16);
+    }
+  }
+  // (row, 16-byte chunk) of the global tile that lane `lane` fetches in wave-load number wl
+  __device__ static __forceinline__ void source_of(int wl, int lane, int* row, int* chunk) {
+    if (IS_V) {
+      const int slot = wl * 64 + lane;  // 16-byte slot within the tile
+      const int piece = slot / (D / 2), sp = slot % (D / 2);
+      *row = 4 * piece + ((sp >> 2) & 3);
+      *chunk = 4 * (sp >> 4) + (sp & 3);
+    } else {
+      const int rpp = KLayout<D>::kRowsPerPiece, cpr = D / 8;
+      *row = wl * rpp + lane / cpr;
+      *chunk = (lane % cpr) ^ KLayout<D>::swz(*row);
+    }
+  }
+  // Same copy for a tile of which only the first `rows` rows exist (the last key block of a sequence
+  // whose length is not a multiple of the tile): the missing rows are fetched from the last row
+  // that exists, so every address stays inside the tensor; their logits are masked by the caller.
+  __device__ __forceinline__ void issue_partial(__amdgpu_buffer_rsrc_t rsrc, int32_t tile_byte_offset, char* lds_tile,
+                                                int wave_in_group, int lane, int64_t stride_l, int rows) const {
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
       const int wl = wave_in_group * kPerWave + u;
       int row, chunk;
-      if (IS_V) {
-        const int slot = wl * 64 + lane;             // 16-byte slot within the tile
-        const int piece = slot / (D / 2), sp = slot % (D / 2);
-        row = 4 * piece + ((sp >> 2) & 3);
-        chunk = 4 * (sp >> 4) + (sp & 3);
-      } else {
-        const int rpp = KLayout<D>::kRowsPerPiece, cpr = D / 8;
-        row = wl * rpp + lane / cpr;
-        chunk = (lane % cpr) ^ KLayout<D>::swz(row);
-      }
-      goff[u] = (int32_t)(row * stride_l * 2 + chunk * 16);
+      source_of(wl, lane, &row, &chunk);
+      if (row >= rows) row = rows - 1;
+      char* dst = lds_tile + lds_piece_offset(wl);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, (int32_t)(row * stride_l * 2 + chunk * 16),
+                                               tile_byte_offset, 0, 0);
     }
   }
   // rsrc: buffer descriptor of the (batch, head) slab; tile_byte_offset: wave-uniform byte offset of
@@ -161,13 +180,18 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, in
 template <int D, int NQ>
 struct QFrag {
   bf16x8 f[NQ][D / 16];
-  __device__ __forceinline__ void load(const __bf16* qrow0, int64_t stride_l, int lane) {
+  // qhead: row 0 of the (batch, head) slab; row0: first row of this wave; rows at or past L (a partial
+  // last query tile) are read from row L-1 and their results dropped by the caller.
+  __device__ __forceinline__ void load(const __bf16* qhead, int row0, int L, int64_t stride_l, int lane) {
     const int j = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
+    for (int nq = 0; nq < NQ; ++nq) {
+      int row = row0 + nq * 32 + j;
+      row = row < L ? row : L - 1;
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk)
-        f[nq][kk] = *reinterpret_cast<const bf16x8*>(qrow0 + (int64_t)(nq * 32 + j) * stride_l + kk * 16 + g * 8);
+        f[nq][kk] = *reinterpret_cast<const bf16x8*>(qhead + (int64_t)row * stride_l + kk * 16 + g * 8);
+    }
   }
 };
 

@@ -40,13 +40,16 @@ struct TileF32 {
   static constexpr int kVFloats = kTileKF * D;
 
   // Cooperative copy of a [32, D] tile (row stride stride_l) into LDS with row stride dst_stride.
+  // Only the first `rows` rows exist (fewer than 32 in the last tile of a sequence whose length is
+  // not a multiple of 32); the others are filled from the last existing row and masked by the caller.
   template <int NT>
   __device__ static __forceinline__ void stage(const float* tile, int64_t stride_l, float* lds,
-                                               int dst_stride, int tid) {
+                                               int dst_stride, int tid, int rows) {
     constexpr int kVec = kTileKF * D / 4;  // float4 pieces
     for (int id = tid; id < kVec; id += NT) {
       const int row = id / (D / 4), c4 = id % (D / 4);
-      const f32x4 x = *reinterpret_cast<const f32x4*>(tile + (int64_t)row * stride_l + c4 * 4);
+      const int src = row < rows ? row : rows - 1;
+      const f32x4 x = *reinterpret_cast<const f32x4*>(tile + (int64_t)src * stride_l + c4 * 4);
       float* dst = lds + row * dst_stride + c4 * 4;
       dst[0] = x[0];
       dst[1] = x[1];
@@ -60,9 +63,11 @@ struct TileF32 {
 template <int D>
 struct QFragF32 {
   float f[D / 2];
-  __device__ __forceinline__ void load(const float* qrow0, int64_t stride_l, int lane) {
+  // qhead: row 0 of the (batch, head) slab; rows at or past L are read from row L-1 (results dropped by the caller)
+  __device__ __forceinline__ void load(const float* qhead, int row0, int L, int64_t stride_l, int lane) {
     const int j = lane & 31, g = lane >> 5;
-    const float* r = qrow0 + (int64_t)j * stride_l;
+    const int row = row0 + j < L ? row0 + j : L - 1;
+    const float* r = qhead + (int64_t)row * stride_l;
 #pragma unroll
     for (int kk = 0; kk < D / 2; ++kk) f[kk] = r[2 * kk + g];
   }

@@ -70,8 +70,10 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_attn_dense(R(_t(sl=66)), R(k), R(v), R(o), None) == 4               # stride
     big = _t(L=1 << 20, sl=1 << 12)                                                        # slab of 2^34 bytes
     assert lib.sparsed_attn_dense(R(big), R(big), R(big), R(big), None) == 4
-    assert lib.sparsed_attn_dense(R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), R(_t(L=48)), None) == 2   # L % 32
-    assert b"L 48" in lib.sparsed_last_error()
+    # a length that is not a block multiple is legal; its index must count the partial last blocks
+    r = _t(L=250)
+    assert lib.sparsed_attn_sparse(R(r), R(r), R(r), R(_ix(nqb=7, nkb=7)), R(r), None) == 8    # floor(250/32) is one short
+    assert b"does not describe" in lib.sparsed_last_error()
     ix = _ix()
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.0, R(ix), None) == 5           # rho
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 1.5, R(ix), None) == 5
@@ -94,4 +96,6 @@ def test_workspace_size_formula():
     t = _t(B=1, H=32, L=65536, D=128, dtype=binding.SPARSED_BF16)
     need = lib.sparsed_select_workspace_bytes(ctypes.byref(t), 128, 64)
     assert need == 32 * 65536 * 4 + 32 * 512 * 1024 * 4
-    assert lib.sparsed_select_workspace_bytes(ctypes.byref(t), 100, 64) == 0
+    r = _t(B=1, H=2, L=250, D=64)
+    assert lib.sparsed_select_workspace_bytes(ctypes.byref(r), 32, 32) == 2048 + 2 * 8 * 8 * 4   # ceil(250/32) = 8 blocks each way
+    assert lib.sparsed_select_workspace_bytes(ctypes.byref(t), 0, 64) == 0

@@ -163,7 +163,7 @@ def test_index_validate_flags_malformed_rows():
 # ----------------------------------------------------------------------------- selection (Section 3.3, Eq. 6)
 def _check_selection(q, k, bq, bk, rho, use_lse, what):
     B, Hq, L, D = q.shape
-    nqb, nkb = L // bq, L // bk
+    nqb, nkb = -(-L // bq), -(-L // bk)
     qd, kd = _dev(q, k)
     pooled = torch.empty(B, Hq, nqb, nkb, dtype=torch.float32, device=DEV)
     lse = None
@@ -246,6 +246,94 @@ def test_closed_form_w1_embedded_in_head_dim_64():
     np.testing.assert_allclose(want[0, 0, rows, 0], g["dense"], atol=1e-6)
     got = sd.attn_dense(*_dev(q, k, v))
     np.testing.assert_allclose(got.cpu().double().numpy()[0, 0, rows, 0], g["dense"], atol=1e-5)
+
+# ----------------------------------------------------------------------------- sequence lengths that are not block multiples
+@pytest.mark.parametrize("dtype,L,Hq,Hkv,D", [
+    (torch.bfloat16, 200, 2, 1, 128),    # 64-row groups; 3 full key tiles + 8 keys
+    (torch.bfloat16, 1000, 2, 2, 128),   # 128-row groups; last key tile has 40 keys
+    (torch.bfloat16, 1100, 1, 1, 128),   # 256-row groups; last key tile has 12 keys (second sub-tile empty)
+    (torch.bfloat16, 65, 2, 2, 64),      # one key in the last tile
+    (torch.bfloat16, 31, 1, 1, 128),     # a single partial tile
+    (torch.bfloat16, 97, 1, 1, 64),      # 33 keys in the last tile: one key in its second sub-tile
+    (torch.float32, 100, 2, 1, 64),
+    (torch.float32, 47, 2, 2, 128),
+    (torch.float32, 333, 1, 1, 64),
+])
+def test_dense_ragged_length(dtype, L, Hq, Hkv, D):
+    _say(f"dense ragged {dtype} L={L} Hq={Hq} Hkv={Hkv} D={D}")
+    q, k, v = _rand_qkv(1, Hq, Hkv, L, D, dtype, seed=L, scale=1.0 if dtype == torch.float32 and D == 64 else None)
+    lse = torch.full((1, Hq, L), float("nan"), dtype=torch.float32, device=DEV)
+    guard = torch.full((1, Hq, L + 300, D), 7.0, dtype=dtype, device=DEV)   # room behind the output: must stay untouched
+    out = guard[:, :, :L]
+    got = sd.attn_dense(*_dev(q, k, v), out=out, lse_out=lse)
+    torch.cuda.synchronize()
+    assert_output_close(got, oracle.attn_dense(q, k, v), dtype, "dense ragged")
+    assert (guard[:, :, L:] == 7.0).all(), "rows past L were written"
+    logits = (q.double() @ k.double().repeat_interleave(Hq // Hkv, 1).transpose(-1, -2)) / math.sqrt(D)
+    want_lse = torch.logsumexp(logits, dim=-1)
+    assert (lse.cpu().double() - want_lse).abs().max() < (2e-5 if dtype == torch.float32 else 1e-4)
+
+
+@pytest.mark.parametrize("dtype,bq,bk,L,Hq,Hkv,D,rho,use_lse", [
+    (torch.bfloat16, 128, 64, 1000, 2, 2, 128, 0.25, False),
+    (torch.bfloat16, 64, 64, 1100, 2, 1, 128, 0.2, True),
+    (torch.bfloat16, 32, 64, 200, 2, 2, 64, 0.5, False),
+    (torch.float32, 32, 32, 100, 2, 2, 64, 0.5, False),
+    (torch.float32, 64, 64, 333, 1, 1, 64, 0.3, True),      # last 64-key block: 13 keys, its second 32-key tile is empty
+    (torch.float32, 128, 32, 300, 2, 1, 128, 0.3, False),
+])
+def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_lse):
+    _say(f"select+sparse ragged {dtype} {bq}x{bk} L={L}")
+    q, k, v = _rand_qkv(1, Hq, Hkv, L, D, dtype, seed=L + bq, scale=1.0 if dtype == torch.float32 and D == 64 else 0.45)
+    ix = _check_selection(q, k, bq, bk, rho, use_lse, f"select ragged L={L}")
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    qd, kd, vd = _dev(q, k, v)
+    # the GPU's own pattern
+    rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    assert_output_close(got, oracle.attn_sparse(q, k, v, rp, ci, bq, bk), dtype, "sparse ragged (selected)")
+    # a pattern in which EVERY row keeps the partial last key block, plus random others, some rows only that block
+    rng = np.random.default_rng(L)
+    rows = []
+    for I in range(Hq * nqb):
+        others = rng.choice(nkb - 1, size=int(rng.integers(0, min(4, nkb - 1) + 1)), replace=False) if nkb > 1 else []
+        rows.append(sorted(set(int(x) for x in others) | {nkb - 1}))
+    cap = max(sum(len(r) for r in rows[h * nqb:(h + 1) * nqb]) for h in range(Hq))
+    rp = np.zeros((1, Hq, nqb + 1), np.int32)
+    ci = np.zeros((1, Hq, cap), np.int32)
+    for h in range(Hq):
+        pos = 0
+        for I in range(nqb):
+            r = rows[h * nqb + I]
+            ci[0, h, pos:pos + len(r)] = r
+            pos += len(r)
+            rp[0, h, I + 1] = pos
+    ix2 = sd.BlockIndex(torch.from_numpy(rp).to(DEV), torch.from_numpy(ci).to(DEV), bq, bk, nkb)
+    sd.index_validate(ix2)
+    guard = torch.full((1, Hq, L + 200, D), 7.0, dtype=dtype, device=DEV)
+    got = sd.attn_sparse(qd, kd, vd, ix2, out=guard[:, :, :L])
+    torch.cuda.synchronize()
+    assert_output_close(got, oracle.attn_sparse(q, k, v, rp, ci, bq, bk), dtype, "sparse ragged (last block in every row)")
+    assert (guard[:, :, L:] == 7.0).all(), "rows past L were written"
+
+
+def test_window_index_ragged_length():
+    from oracle import patterns
+    for L, bq, bk, window, sink in [(1000, 128, 64, 256, 70), (333, 32, 32, 50, 0)]:
+        # the token-level definition on the padded grid, cut back to the L real tokens
+        nqb, nkb = -(-L // bq), -(-L // bk)
+        m = patterns.window_token_mask(L, window, sink)
+        blocks = np.zeros((nqb, nkb), bool)
+        for I in range(nqb):
+            for J in range(nkb):
+                blocks[I, J] = m[I * bq:(I + 1) * bq, J * bk:(J + 1) * bk].any()
+        ptr, col = patterns.rows_to_csr([np.nonzero(r)[0].astype(np.int32) for r in blocks], 2)
+        ix = sd.index_fill_window(1, 2, L, bq, bk, window, sink, DEV)
+        sd.index_validate(ix)
+        assert np.array_equal(ix.row_ptr.cpu().numpy().reshape(2, -1), ptr)
+        assert np.array_equal(ix.row_ptr.cpu().numpy().reshape(2, -1)[:, -1], [col.shape[1]] * 2)
+        assert np.array_equal(ix.col_idx.cpu().numpy().reshape(2, -1)[:, :col.shape[1]], col)
+
 
 # ----------------------------------------------------------------------------- fixed patterns (Section 4.1 baselines)
 @pytest.mark.parametrize("L,bq,bk,window,sink", [
