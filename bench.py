@@ -92,6 +92,15 @@ def cpu_baseline(cfg, q, k, v, index, keep, budget_s=15.0):
     return out
 
 
+def _select_bytes(cfg, keep):
+    """Algorithmic bytes of one selection call that reuses the dense call's statistics."""
+    esz = 2 if cfg.dtype == "bf16" else 4
+    qk = (cfg.B * cfg.Hq + cfg.B * cfg.Hkv) * cfg.L * cfg.d * esz
+    lse = cfg.B * cfg.Hq * cfg.L * 4
+    index = cfg.B * cfg.Hq * (cfg.nqb * keep + cfg.nqb + 1) * 4
+    return qk + lse + index
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,7 +247,9 @@ def main():
         "roofline_dense": {"kernel": "attn_dense", "bound": "mfma", "achieved": dense_tf, "peak": peak, "unit": "TFLOP/s",
                            "frac": dense_tf / peak},
         "roofline_select": {"kernel": "select_pattern (pooled scores + top-k, statistics reused)", "bound": "mfma",
-                            "achieved": select_tf, "peak": peak, "unit": "TFLOP/s", "frac": select_tf / peak},
+                            "achieved": select_tf, "peak": peak, "unit": "TFLOP/s", "frac": select_tf / peak,
+                            # the same call as memory traffic: Q and K read once, row statistics read, index written
+                            "hbm_algorithmic_GBps": _select_bytes(cfg, keep) / (select_ms * 1e-3) / 1e9},
     }
     if cfg.dtype == "bf16":
         # What the matrix cores sustain on their own (no LDS, no vector work): all-zero operands reach the published
