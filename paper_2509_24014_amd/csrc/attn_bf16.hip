@@ -71,9 +71,6 @@ __global__ __launch_bounds__(NW * 64)
   const int tail_keys = a.L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
   auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
-  QFrag<D, NQ> qf;
-  qf.load(qbase, row0, a.L, a.q.sl, lane);
-
   float M[NQ], lsum[NQ];
   f32x16 o[NQ][D / 32];
 #pragma unroll
@@ -109,6 +106,10 @@ __global__ __launch_bounds__(NW * 64)
     return cols[idx + opaque_zero];
   };
   int blk0 = col_at(0), blk1 = col_at(1), blk2 = col_at(2), blk3 = col_at(3);
+  // Q after the block numbers: the loads complete in issue order, so the first K/V copies (which
+  // need blk0, blk1) can start while the Q rows are still on their way.
+  QFrag<D, NQ> qf;
+  qf.load(qbase, row0, a.L, a.q.sl, lane);
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
   const int64_t slab_rows = (int64_t)(a.L - 1);
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
@@ -270,17 +271,22 @@ __global__ __launch_bounds__(NW * 64)
   }
 #undef SPARSED_TILE_STEP
 
-  // combine the two half-row sums, normalise, store
+  // Combine the two half-row sums, normalise, store. In the accumulator a lane holds 4 consecutive
+  // output columns of ONE row at a time, so direct stores would be 8-byte pieces scattered over 32
+  // rows. Each wave instead passes its 32 x D tile through its own slice of the (now idle) K/V
+  // buffers and writes whole rows: 16 bytes per lane, D/8 lanes per row. The slice keeps 16-byte
+  // slot c of row r at position c ^ (r mod slots) so that neither side has bank conflicts beyond 2-way.
+  constexpr int kRowBytes = 2 * D, kSlots = D / 8, kRowsPerStore = 64 / kSlots;
+  static_assert(32 * kRowBytes * 2 <= kKBytes && (!kHasV || 32 * kRowBytes * 2 <= kVBytes), "two waves share one buffer");
+  char* const stage = ((wave >> 1) == 0 ? kbuf0 : (wave >> 1) == 1 ? kbuf1 : (wave >> 1) == 2 ? vbuf0 : vbuf1) + (wave & 1) * (32 * kRowBytes);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const float ltot = pair_sum(lsum[nq]);
     const int row = row0 + nq * 32 + j;
-    if (row >= a.L) continue;  // partial last query tile
-    if (a.lse != nullptr && g == 0)
+    if (a.lse != nullptr && g == 0 && row < a.L)
       a.lse[(int64_t)bh * a.L + row] = (M[nq] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
     if (kHasV) {
       const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
-      __bf16* orow = static_cast<__bf16*>(a.o) + b * a.o_sb + h * a.o_sh + (int64_t)row * a.o_sl;
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
@@ -290,8 +296,17 @@ __global__ __launch_bounds__(NW * 64)
           u32x2 w;
           w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
           w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-          *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q4 + 4 * g) = w;
+          // columns 32*dt + 8*q4 + 4*g .. +3 of row j: slot 4*dt + q4, half g
+          *reinterpret_cast<u32x2*>(stage + j * kRowBytes + (((4 * dt + q4) ^ (j & (kSlots - 1))) << 4) + 8 * g) = w;
         }
+      __bf16* const obase = static_cast<__bf16*>(a.o) + b * a.o_sb + h * a.o_sh;
+#pragma unroll
+      for (int it = 0; it < 32 / kRowsPerStore; ++it) {
+        const int r = it * kRowsPerStore + lane / kSlots, slot = lane % kSlots;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(stage + r * kRowBytes + ((slot ^ (r & (kSlots - 1))) << 4));
+        const int grow = row0 + nq * 32 + r;
+        if (grow < a.L) *reinterpret_cast<u32x4*>(obase + (int64_t)grow * a.o_sl + slot * 8) = w;  // partial last query tile: rows past L are dropped
+      }
     }
   }
 #endif
