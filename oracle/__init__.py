@@ -158,6 +158,49 @@ def select_isolated(apool: np.ndarray, rho: float, n_pre: int):
     return row_ptr, col_idx
 
 
+def prefill_ranges(L: int, bk: int, prefill_tokens: int):
+    """Key ranges for isolated selection with the boundary at a key token: one range per key block,
+    except that the block holding the boundary is split in two. Returns (vstart, vend, vblock, n_pre)."""
+    nkb = -(-L // bk)
+    vstart, vend, vblock = [], [], []
+    for J in range(nkb):
+        lo, hi = J * bk, min((J + 1) * bk, L)
+        if lo < prefill_tokens < hi:
+            vstart += [lo, prefill_tokens]
+            vend += [prefill_tokens, hi]
+            vblock += [J, J]
+        else:
+            vstart.append(lo)
+            vend.append(hi)
+            vblock.append(J)
+    n_pre = sum(1 for e in vend if e <= prefill_tokens)
+    i32 = lambda x: np.asarray(x, dtype=np.int32)  # noqa: E731
+    return i32(vstart), i32(vend), i32(vblock), n_pre
+
+
+def select_isolated_tokens(q, k, bq: int, bk: int, rho: float, prefill_tokens: int):
+    """Eq. 5 + Eq. 6 with the prefill / generation boundary at key token ``prefill_tokens``.
+
+    Returns (row_ptr [B,H,nqb+1], col_idx [B,H,cap], apool_ranges [B,H,nqb,nv], n_pre, vblock);
+    rows may differ in length by one (the block holding the boundary can be kept by both ranges)."""
+    q, k = _f32(q), _f32(k)
+    B, Hq, Hkv, L, d = _dims(q, k)
+    vstart, vend, vblock, n_pre = prefill_ranges(L, bk, prefill_tokens)
+    nv, nqb = len(vstart), -(-L // bq)
+    ap = np.empty((B, Hq, nqb, nv), dtype=np.float64)
+    lib = _load()
+    _check(lib.oracle_pool_scores_ranges(_p(q), _p(k), B, Hq, Hkv, L, d, bq, nv, _p(vstart), _p(vend), _p(ap)), "pool_scores_ranges")
+    keep = (kept_blocks(rho, n_pre) if n_pre > 0 else 0) + (kept_blocks(rho, nv - n_pre) if nv > n_pre else 0)
+    cap = nqb * keep
+    row_ptr = np.empty((B, Hq, nqb + 1), dtype=np.int32)
+    col_idx = np.full((B, Hq, cap), -1, dtype=np.int32)
+    f = lib.oracle_select_isolated_ranges
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                  ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    _check(f(_p(ap), B, Hq, nqb, nv, float(rho), int(n_pre), _p(vblock), cap, _p(row_ptr), _p(col_idx)), "select_isolated_ranges")
+    return row_ptr, col_idx, ap, n_pre, vblock
+
+
 def select_pattern(q, k, bq: int, bk: int, rho: float):
     """Pooling + Eq. 6: what the selection step of Algorithm 1 produces.
 

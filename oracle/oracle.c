@@ -307,6 +307,89 @@ int oracle_select_isolated(const double* apool, int B, int Hq, int nqb, int nkb,
   return 0;
 }
 
+/* ---- Eq. 5 + Eq. 6 with the prefill / generation boundary at a key TOKEN ----- */
+/* The paper splits the keys into the prefill tokens [0, p) and the generation
+ * tokens [p, L) and ranks each range on its own (Eq. 5, Eq. 6); it does not say
+ * what happens when p falls inside a key block. Reading taken here: the block
+ * that holds p is pooled twice, once over its prefill keys and once over its
+ * generation keys (each a mean over the entries that exist), and competes in
+ * both ranges; it is kept if either range keeps it.
+ *
+ * oracle_pool_scores_ranges: mean of A over (query block I) x (keys [vstart[v], vend[v]))
+ * for nv arbitrary key ranges; out is [B, Hq, nqb, nv] doubles.                 */
+int oracle_pool_scores_ranges(const float* q, const float* k, int B, int Hq, int Hkv, int L, int d,
+                              int bq, int nv, const int32_t* vstart, const int32_t* vend, double* out) {
+  int rc = check_shape(B, Hq, Hkv, L, d);
+  if (rc) return rc;
+  if (bq <= 0 || nv <= 0) return -4;
+  for (int v = 0; v < nv; ++v)
+    if (vstart[v] < 0 || vend[v] > L || vstart[v] >= vend[v]) return -4;
+  const int nqb = (L + bq - 1) / bq;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double* p = (double*)malloc((size_t)L * sizeof(double));
+    if (!p) {
+#pragma omp atomic write
+      fail = 1;
+    }
+#pragma omp for schedule(dynamic, 1)
+    for (long u = 0; u < (long)B * Hq * nqb; ++u) {
+      if (!p) continue;
+      const int I = (int)(u % nqb);
+      const int h = (int)((u / nqb) % Hq), b = (int)(u / nqb / Hq);
+      const float* khead = k + IDX4(b, h / (Hq / Hkv), 0, Hkv, L, d);
+      double* arow = out + (size_t)u * nv;
+      for (int v = 0; v < nv; ++v) arow[v] = 0.0;
+      const int rows = (I * bq + bq <= L) ? bq : L - I * bq;
+      for (int r = 0; r < rows; ++r) {
+        probs_row(q + IDX4(b, h, I * bq + r, Hq, L, d), khead, L, d, p);
+        for (int v = 0; v < nv; ++v)
+          for (int j = vstart[v]; j < vend[v]; ++j) arow[v] += p[j];
+      }
+      for (int v = 0; v < nv; ++v) arow[v] /= (double)rows * (double)(vend[v] - vstart[v]);
+    }
+    free(p);
+  }
+  return fail ? -9 : 0;
+}
+
+/* Ranks the ranges [0, n_pre) and [n_pre, nv) of every pooled row separately,
+ * keeps oracle_kept_blocks(rho, size) of each, maps range v to key block vblock[v]
+ * (two neighbouring ranges may map to the same block) and writes the union,
+ * ascending and without duplicates, as CSR: rows may differ in length by one.
+ * row_ptr [B, Hq, nqb+1], col_idx [B, Hq, cap] with cap >= nqb * (keep_pre + keep_gen). */
+int oracle_select_isolated_ranges(const double* apool, int B, int Hq, int nqb, int nv, double rho, int n_pre,
+                                  const int32_t* vblock, int cap, int32_t* row_ptr, int32_t* col_idx) {
+  if (B <= 0 || Hq <= 0 || nqb <= 0 || nv <= 0 || n_pre < 0 || n_pre > nv) return -1;
+  const int keep_pre = oracle_kept_blocks(rho, n_pre);
+  const int keep_gen = oracle_kept_blocks(rho, nv - n_pre);
+  if (cap < nqb * (keep_pre + keep_gen)) return -1;
+  unsigned char* mark = (unsigned char*)malloc((size_t)nv);
+  if (!mark) return -9;
+  for (long bh = 0; bh < (long)B * Hq; ++bh) {
+    int32_t* rp = row_ptr + (size_t)bh * (nqb + 1);
+    int32_t* cols = col_idx + (size_t)bh * cap;
+    int n = 0;
+    rp[0] = 0;
+    for (int I = 0; I < nqb; ++I) {
+      const double* arow = apool + ((size_t)bh * nqb + I) * nv;
+      memset(mark, 0, (size_t)nv);
+      if (keep_pre > 0) mark_topk(arow, 0, n_pre, keep_pre, mark, NULL, NULL);
+      if (keep_gen > 0) mark_topk(arow, n_pre, nv, keep_gen, mark, NULL, NULL);
+      const int row_begin = n;
+      for (int v = 0; v < nv; ++v) {
+        if (!mark[v]) continue;
+        if (n > row_begin && cols[n - 1] == vblock[v]) continue; /* the straddling block, kept by both ranges */
+        cols[n++] = vblock[v];
+      }
+      rp[I + 1] = n;
+    }
+  }
+  free(mark);
+  return 0;
+}
+
 /* ---- Eq. 3 + Eq. 4 as a set restriction: one query block -------------------- */
 /* Rows of query block I attend only to keys in the listed key blocks; max, sum
  * and the weighted V-sum run over those keys only. An empty list gives zeros.

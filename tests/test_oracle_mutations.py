@@ -42,6 +42,12 @@ MUTANTS = [
      "        if (j >= L) {\n          s[t * bk + c] = -INFINITY;\n          continue;\n        }",
      "        if (j >= L) {\n          s[t * bk + c] = 0.0;\n          continue;\n        }",
      [lambda: pins.test_ragged_sparse_matches_bruteforce_and_dense()]),
+    ("token boundary: the block kept by both ranges is listed twice",
+     "        if (n > row_begin && cols[n - 1] == vblock[v]) continue; /* the straddling block, kept by both ranges */\n", "",
+     [lambda: pins.test_token_boundary_rows_are_unions_of_per_range_optima()]),
+    ("range pooling: divided by the block size instead of the range length",
+     "arow[v] /= (double)rows * (double)(vend[v] - vstart[v]);", "arow[v] /= (double)rows * 16.0;",
+     [lambda: pins.test_range_pooling_matches_sliced_means_of_torch_probs()]),
     ("count rule: floor instead of guarded ceil",
      "int kk = (int)ceil(rho * (double)n - 1e-9);", "int kk = (int)floor(rho * (double)n);",
      [lambda: pins.test_kept_blocks_rule()]),

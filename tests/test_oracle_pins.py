@@ -363,6 +363,62 @@ def test_ragged_selection_counts_blocks_with_ceil():
         assert set(ci[0, 0, 3 * I: 3 * I + 3]) == set(np.argsort(-ap[0, 0, I], kind="stable")[:3])
 
 
+# ----------------------------------------------------------------------------- isolated selection, boundary at a token
+def test_range_pooling_matches_sliced_means_of_torch_probs():
+    L, bq, bk, ptok = 90, 16, 16, 40                       # the boundary falls inside key block 2; the last block is partial
+    q, k, _ = _rand(1, 2, 1, L, 8, seed=41)
+    _, _, ap, n_pre, vblock = oracle.select_isolated_tokens(q, k, bq, bk, 0.4, ptok)
+    vstart, vend, vb, n_pre2 = oracle.prefill_ranges(L, bk, ptok)
+    assert vstart.tolist() == [0, 16, 32, 40, 48, 64, 80] and vend.tolist() == [16, 32, 40, 48, 64, 80, 90]
+    assert vb.tolist() == [0, 1, 2, 2, 3, 4, 5] == vblock.tolist() and n_pre == n_pre2 == 3
+    P = _torch_probs(q, k)
+    for I in range(6):
+        rows = P[:, :, I * bq:min((I + 1) * bq, L)]
+        for v in range(7):
+            want = rows[..., vstart[v]:vend[v]].mean(dim=(-1, -2)).numpy()
+            np.testing.assert_allclose(ap[:, :, I, v], want, rtol=1e-12)
+    # every probability is counted exactly once: sum of (mean x area) over the ranges = number of rows
+    area = (vend - vstart).astype(np.float64)
+    rows = np.array([16] * 5 + [10], dtype=np.float64)
+    np.testing.assert_allclose((ap * area).sum(-1) * rows, np.broadcast_to(rows, ap.shape[:-1]), rtol=1e-12)
+
+
+def test_token_boundary_on_a_block_edge_reduces_to_the_block_version():
+    q, k, _ = _rand(1, 2, 2, 96, 8, seed=42)
+    rp, ci, ap, n_pre, vblock = oracle.select_isolated_tokens(q, k, 16, 16, 0.34, 32)
+    a = oracle.pool_scores(q, k, 16, 16)
+    rp2, ci2 = oracle.select_isolated(a, 0.34, 2)
+    assert n_pre == 2 and vblock.tolist() == list(range(6))
+    np.testing.assert_allclose(ap, a, rtol=1e-13)
+    assert np.array_equal(rp, rp2) and np.array_equal(ci, ci2)
+    # no prefill at all / everything prefill: plain selection
+    for ptok in (0, 96):
+        rp3, ci3, _, _, _ = oracle.select_isolated_tokens(q, k, 16, 16, 0.34, ptok)
+        rp4, ci4, _ = oracle.select_topk(a, oracle.kept_blocks(0.34, 6))
+        assert np.array_equal(rp3, rp4) and np.array_equal(ci3, ci4)
+
+
+def test_token_boundary_rows_are_unions_of_per_range_optima():
+    L, bq, bk, ptok, rho = 96, 16, 16, 40, 0.34
+    q, k, _ = _rand(1, 3, 1, L, 8, seed=43)
+    rp, ci, ap, n_pre, vblock = oracle.select_isolated_tokens(q, k, bq, bk, rho, ptok)
+    nv = ap.shape[-1]
+    keep_pre, keep_gen = oracle.kept_blocks(rho, n_pre), oracle.kept_blocks(rho, nv - n_pre)
+    lengths = set()
+    for h in range(3):
+        assert rp[0, h, 0] == 0
+        for I in range(L // bq):
+            row = ci[0, h, rp[0, h, I]:rp[0, h, I + 1]].tolist()
+            assert row == sorted(set(row)), "ascending, no duplicates"
+            a = ap[0, h, I]
+            best_pre = max(itertools.combinations(range(n_pre), keep_pre), key=lambda c: sum(a[list(c)]))
+            best_gen = max(itertools.combinations(range(n_pre, nv), keep_gen), key=lambda c: sum(a[list(c)]))
+            want = sorted({int(vblock[v]) for v in best_pre + best_gen})
+            assert row == want
+            lengths.add(len(row))
+    assert lengths <= {keep_pre + keep_gen, keep_pre + keep_gen - 1} and len(lengths) == 2   # both cases occur for this seed
+
+
 def test_closed_form_w1():
     g = _read_golden("w1_closed_form.txt")
     L = 4
