@@ -154,6 +154,25 @@ sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sp
                                                const sparsed_exec* ex);
 
 /*
+ * Isolated selection with the boundary given as a key TOKEN (Eq. 5 splits the keys
+ * into prefill tokens [0, prefill_tokens) and generation tokens [prefill_tokens, L)).
+ * On a block edge this is sparsed_select_pattern_isolated. Otherwise the paper is
+ * silent; reading: the key block that holds the boundary is pooled twice, over its
+ * prefill keys and over its generation keys (each a mean over the entries that
+ * exist), competes in both ranges with those scores, and is listed once if either
+ * range keeps it. With n_pre = ceil(prefill_tokens / block_k) and n_gen = nkb -
+ * floor(prefill_tokens / block_k), the ranges keep sparsed_kept_blocks(rho, n_pre)
+ * and sparsed_kept_blocks(rho, n_gen) entries; a row has their sum or one fewer, so
+ * row_ptr is not I*k here. cap_per_head must be >= nqb * (the sum). Workspace:
+ * sparsed_select_tokens_workspace_bytes().
+ */
+sparsed_status sparsed_select_pattern_isolated_tokens(const sparsed_tensor* q, const sparsed_tensor* k,
+                                                      int32_t block_q, int32_t block_k, double rho,
+                                                      int32_t prefill_tokens,
+                                                      sparsed_block_index* out_block_index,
+                                                      const sparsed_exec* ex);
+
+/*
  * Fixed pattern of the paper's sparse baselines (Section 4.1: sliding window, and
  * StreamingLLM = window + leading "sink" keys) written as a block index, so the
  * same sparse kernel runs them: query block I keeps every key block holding a
@@ -184,6 +203,9 @@ int32_t sparsed_n_dense_steps(int32_t T, double skip);
 
 /* Bytes of workspace sparsed_select_pattern needs for this q and these blocks (0 on bad arguments). */
 size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);
+
+/* The same for sparsed_select_pattern_isolated_tokens (a little more: two extra pooled columns and row staging). */
+size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);
 
 /*
  * Checks on the device that every row of the index is in range, strictly

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     n_dense_steps,
     select_pattern,
     select_pattern_isolated,
+    select_pattern_isolated_tokens,
     select_workspace_bytes,
     version,
 )

@@ -24,6 +24,7 @@ EXPORTS = [
     "sparsed_kept_blocks", "sparsed_n_dense_steps", "sparsed_select_workspace_bytes", "sparsed_index_validate",
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
     "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16",
+    "sparsed_select_pattern_isolated_tokens", "sparsed_select_tokens_workspace_bytes",
 ]
 
 
@@ -72,6 +73,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_select_pattern.restype = ctypes.c_int
     lib.sparsed_select_pattern_isolated.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, I, E]
     lib.sparsed_select_pattern_isolated.restype = ctypes.c_int
+    lib.sparsed_select_pattern_isolated_tokens.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, I, E]
+    lib.sparsed_select_pattern_isolated_tokens.restype = ctypes.c_int
+    lib.sparsed_select_tokens_workspace_bytes.argtypes = [T, ctypes.c_int32, ctypes.c_int32]
+    lib.sparsed_select_tokens_workspace_bytes.restype = ctypes.c_size_t
     lib.sparsed_attn_sparse.argtypes = [T, T, T, I, T, E]
     lib.sparsed_attn_sparse.restype = ctypes.c_int
     lib.sparsed_kept_blocks.argtypes = [ctypes.c_double, ctypes.c_int32]
@@ -184,11 +189,13 @@ def attn_dense(q, k, v, out: Optional[torch.Tensor] = None, lse_out: Optional[to
     return out
 
 
-def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pooled_out, index, stream):
+def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pooled_out, index, stream, prefill_tokens=None):
     lib = load_library()
     B, H, L, D = q.shape
     nqb, nkb = -(-L // block_q), -(-L // block_k)
-    if prefill_blocks is None:
+    if prefill_tokens is not None:
+        keep = kept_blocks(rho, -(-prefill_tokens // block_k)) + kept_blocks(rho, nkb - prefill_tokens // block_k)
+    elif prefill_blocks is None:
         keep = kept_blocks(rho, nkb)
     else:
         keep = kept_blocks(rho, prefill_blocks) + kept_blocks(rho, nkb - prefill_blocks)
@@ -196,7 +203,9 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
         index = BlockIndex(torch.empty(B, H, nqb + 1, dtype=torch.int32, device=q.device),
                            torch.empty(B, H, max(nqb * keep, 1), dtype=torch.int32, device=q.device), block_q, block_k, nkb)
     if workspace is None:
-        need = select_workspace_bytes(q, block_q, block_k)
+        tq0 = _tensor(q, "q")
+        need = (select_workspace_bytes(q, block_q, block_k) if prefill_tokens is None
+                else int(lib.sparsed_select_tokens_workspace_bytes(ctypes.byref(tq0), block_q, block_k)))
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     if pooled_out is not None and (pooled_out.dtype != torch.float32 or not pooled_out.is_contiguous()
                                    or pooled_out.numel() != B * H * nqb * nkb):
@@ -206,7 +215,10 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
     ex = _Exec(_stream_ptr(stream), workspace.data_ptr(), workspace.numel() * workspace.element_size(), None,
                lse_in.data_ptr() if lse_in is not None else None, pooled_out.data_ptr() if pooled_out is not None else None)
     tq, tk, ci = _tensor(q, "q"), _tensor(k, "k"), index._c()
-    if prefill_blocks is None:
+    if prefill_tokens is not None:
+        st = lib.sparsed_select_pattern_isolated_tokens(ctypes.byref(tq), ctypes.byref(tk), block_q, block_k, float(rho),
+                                                        int(prefill_tokens), ctypes.byref(ci), ctypes.byref(ex))
+    elif prefill_blocks is None:
         st = lib.sparsed_select_pattern(ctypes.byref(tq), ctypes.byref(tk), block_q, block_k, float(rho), ctypes.byref(ci),
                                         ctypes.byref(ex))
     else:
@@ -226,6 +238,12 @@ def select_pattern_isolated(q, k, block_q: int, block_k: int, rho: float, prefil
                             pooled_out=None, index: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
     """sparsed_select_pattern_isolated: separate top-rho% over prefill and generation key blocks."""
     return _select(q, k, block_q, block_k, rho, int(prefill_blocks), lse_in, workspace, pooled_out, index, stream)
+
+
+def select_pattern_isolated_tokens(q, k, block_q: int, block_k: int, rho: float, prefill_tokens: int, lse_in=None,
+                                   workspace=None, pooled_out=None, index: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
+    """sparsed_select_pattern_isolated_tokens: isolated selection with the boundary at a key token."""
+    return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, prefill_tokens=int(prefill_tokens))
 
 
 def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, stream=None):

@@ -123,6 +123,13 @@ size_t select_ws_bytes(int B, int Hq, int L, int nqb, int nkb) {
   return align256((size_t)B * Hq * L * sizeof(float)) + align256((size_t)B * Hq * nqb * nkb * sizeof(float));
 }
 
+// Extra scratch when the prefill boundary falls inside a key block: the two partial scores of that
+// block per pooled row, fixed-stride rows of kept blocks (at most nkb + 1 each) and their lengths.
+size_t select_tokens_extra_bytes(int B, int Hq, int nqb, int nkb) {
+  const size_t rows = (size_t)B * Hq * nqb;
+  return align256(rows * 2 * sizeof(float)) + align256(rows * (size_t)(nkb + 1) * sizeof(int32_t)) + align256(rows * sizeof(int32_t));
+}
+
 sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tensor* k, const sparsed_tensor* v,
                          const sparsed_block_index* ix, sparsed_tensor* out, const sparsed_exec* ex) {
   sparsed_status st;
@@ -161,8 +168,11 @@ sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tenso
   return SPARSED_OK;
 }
 
+// boundary_token >= 0: isolated selection whose prefill / generation boundary is that key token and lies
+// strictly inside a key block (prefill_blocks is then ignored).
 sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int32_t bq, int32_t bk, double rho,
-                           int32_t prefill_blocks, bool isolated, sparsed_block_index* ix, const sparsed_exec* ex) {
+                           int32_t prefill_blocks, bool isolated, sparsed_block_index* ix, const sparsed_exec* ex,
+                           int32_t boundary_token = -1) {
   sparsed_status st;
   if ((st = check_tensor(q, "q")) || (st = check_tensor(k, "k")) || (st = check_qk(q, k, "k"))) return st;
   if ((st = check_blocks(q, bq, bk))) return st;
@@ -172,7 +182,12 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   const int nqb = ix->nqb, nkb = ix->nkb;
   if (nkb > 8192) return fail(SPARSED_ERR_UNSUPPORTED, "more than 8192 key blocks per row (%d)", nkb);
   int split = nkb, keep_lo, keep_hi = 0;
-  if (isolated) {
+  const int straddle = boundary_token >= 0 ? boundary_token / bk : -1;  // the key block that holds the boundary
+  if (straddle >= 0) {
+    split = straddle + 1;  // ranked entries: blocks 0 .. straddle (its prefill part), then its generation part and the rest
+    keep_lo = sparsed_kept_blocks(rho, split);
+    keep_hi = sparsed_kept_blocks(rho, nkb - straddle);
+  } else if (isolated) {
     if (prefill_blocks < 0 || prefill_blocks > nkb) return fail(SPARSED_ERR_RANGE, "prefill_blocks %d outside [0, %d]", prefill_blocks, nkb);
     split = prefill_blocks;
     keep_lo = sparsed_kept_blocks(rho, split);
@@ -185,7 +200,8 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
     return fail(SPARSED_ERR_INDEX, "cap_per_head %d < nqb*k = %lld", ix->cap_per_head, (long long)nqb * keep);
 
   const size_t lse_bytes = align256((size_t)q->B * q->H * q->L * sizeof(float));
-  const size_t need = select_ws_bytes(q->B, q->H, q->L, nqb, nkb);
+  const size_t base_bytes = select_ws_bytes(q->B, q->H, q->L, nqb, nkb);
+  const size_t need = base_bytes + (straddle >= 0 ? select_tokens_extra_bytes(q->B, q->H, nqb, nkb) : 0);
   char* ws = nullptr;
   if (ex && ex->workspace) {
     if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ex->workspace_bytes, need);
@@ -228,11 +244,37 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   p.Hkv = k->H;
   p.L = q->L;
   p.nqb = nqb;
-  p.nkb = nkb;
   p.block_k = bk;
+  p.key_begin = 0;
+  p.key_len = q->L;
+  p.out_stride = nkb;
+  p.out_col0 = 0;
   p.scale_log2 = scale_log2(q->D);
   hipError_t e = bf16 ? launch_pool_bf16(q->D, bq, p, s) : launch_pool_f32(q->D, bq, p, s);
   if (e != hipSuccess) return hip_fail(e, "pooled-score launch");
+  const size_t rows = (size_t)q->B * q->H * nqb;
+  float* part = nullptr;
+  int32_t *rows_tmp = nullptr, *counts = nullptr;
+  if (straddle >= 0) {
+    // the block that holds the boundary once more, pooled over its prefill keys and over its generation keys
+    char* extra = ws + base_bytes;
+    part = reinterpret_cast<float*>(extra);
+    rows_tmp = reinterpret_cast<int32_t*>(extra + align256(rows * 2 * sizeof(float)));
+    counts = reinterpret_cast<int32_t*>(extra + align256(rows * 2 * sizeof(float)) + align256(rows * (size_t)(nkb + 1) * sizeof(int32_t)));
+    const int block_end = (straddle + 1) * bk < q->L ? (straddle + 1) * bk : q->L;
+    PoolArgs pa = p;
+    pa.apool = part;
+    pa.out_stride = 2;
+    pa.key_begin = straddle * bk;
+    pa.key_len = boundary_token - straddle * bk;
+    e = bf16 ? launch_pool_bf16(q->D, bq, pa, s) : launch_pool_f32(q->D, bq, pa, s);
+    if (e != hipSuccess) return hip_fail(e, "pooled-score launch (prefill part of the boundary block)");
+    pa.out_col0 = 1;
+    pa.key_begin = boundary_token;
+    pa.key_len = block_end - boundary_token;
+    e = bf16 ? launch_pool_bf16(q->D, bq, pa, s) : launch_pool_f32(q->D, bq, pa, s);
+    if (e != hipSuccess) return hip_fail(e, "pooled-score launch (generation part of the boundary block)");
+  }
   // 3. per-row top-k into the CSR index
   TopkArgs t{};
   t.apool = apool;
@@ -245,8 +287,18 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   t.keep_lo = keep_lo;
   t.keep_hi = keep_hi;
   t.cap_per_head = ix->cap_per_head;
+  t.straddle = straddle;
+  t.part = part;
+  t.rows_tmp = rows_tmp;
+  t.counts = counts;
   e = launch_topk(t, s);
   if (e != hipSuccess) return hip_fail(e, "top-k launch");
+  if (straddle >= 0) {
+    // rows differ in length (the boundary block may be kept by both ranges): build the CSR from the fixed-stride rows
+    CompactArgs c{rows_tmp, counts, ix->row_ptr, ix->col_idx, q->B * q->H, nqb, keep, ix->cap_per_head};
+    e = launch_compact(c, s);
+    if (e != hipSuccess) return hip_fail(e, "index compaction launch");
+  }
   return SPARSED_OK;
 }
 
@@ -274,6 +326,23 @@ sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sp
                                                double rho, int32_t prefill_blocks, sparsed_block_index* out_block_index,
                                                const sparsed_exec* ex) {
   return select_impl(q, k, block_q, block_k, rho, prefill_blocks, true, out_block_index, ex);
+}
+
+sparsed_status sparsed_select_pattern_isolated_tokens(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q,
+                                                      int32_t block_k, double rho, int32_t prefill_tokens,
+                                                      sparsed_block_index* out_block_index, const sparsed_exec* ex) {
+  if (!q) return fail(SPARSED_ERR_NULL, "q is NULL");
+  if (block_k <= 0) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d", block_k);
+  if (prefill_tokens < 0 || prefill_tokens > q->L) return fail(SPARSED_ERR_RANGE, "prefill_tokens %d outside [0, %d]", prefill_tokens, q->L);
+  if (prefill_tokens % block_k == 0 || prefill_tokens == q->L)  // on a block edge: the block form
+    return select_impl(q, k, block_q, block_k, rho, ceil_div(prefill_tokens, block_k), true, out_block_index, ex);
+  return select_impl(q, k, block_q, block_k, rho, 0, true, out_block_index, ex, prefill_tokens);
+}
+
+size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
+  if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
+  const int nqb = ceil_div(q->L, block_q), nkb = ceil_div(q->L, block_k);
+  return select_ws_bytes(q->B, q->H, q->L, nqb, nkb) + select_tokens_extra_bytes(q->B, q->H, nqb, nkb);
 }
 
 int32_t sparsed_kept_blocks(double rho, int32_t n) {

@@ -26,13 +26,17 @@ struct AttnArgs {
   float scale_log2;        // log2(e) / sqrt(D)
 };
 
-// Arguments of the pooled-score kernels (Section 3.3: A' = avgpool(A, block)).
+// Arguments of the pooled-score kernels (Section 3.3: A' = avgpool(A, block)). The keys pooled are
+// the tokens [key_begin, key_begin + key_len), cut into blocks of block_k from key_begin on (the whole
+// sequence for plain selection; one part of the block that holds the prefill boundary otherwise).
 struct PoolArgs {
   TensorArg q, k;
-  const float* lse;        // [B, Hq, L] natural-log sum-exp of each row (from the statistics pass)
-  float* apool;            // [B, Hq, nqb, nkb]
+  const float* lse;        // [B, Hq, L] natural-log sum-exp of each row over ALL L keys
+  float* apool;            // [B, Hq, nqb, out_stride]; block t of the range lands in column out_col0 + t
   int32_t B, Hq, Hkv, L;
-  int32_t nqb, nkb, block_k;
+  int32_t nqb, block_k;
+  int32_t key_begin, key_len;
+  int32_t out_stride, out_col0;
   float scale_log2;        // log2(e) / sqrt(D)
 };
 
@@ -45,6 +49,23 @@ struct TopkArgs {
   int32_t split;           // key blocks [0, split) and [split, nkb) are ranked separately
   int32_t keep_lo, keep_hi;  // kept in each range (keep_hi = 0 and split = nkb for one range)
   int32_t cap_per_head;
+  // Prefill boundary inside key block `straddle` (else straddle < 0): that block enters the first range
+  // with score part[2r] (its prefill keys) and the second with part[2r+1] (its generation keys); it is
+  // listed once even if both keep it, so rows differ in length: entries go to rows_tmp [rows, keep_lo +
+  // keep_hi] and counts [rows], and compact_kernel builds the CSR from them.
+  int32_t straddle;
+  const float* part;
+  int32_t* rows_tmp;
+  int32_t* counts;
+};
+
+// Builds row_ptr / col_idx of every head from fixed-stride rows and their lengths.
+struct CompactArgs {
+  const int32_t* rows_tmp;  // [heads * nqb, stride]
+  const int32_t* counts;    // [heads * nqb]
+  int32_t* row_ptr;         // [heads, nqb + 1]
+  int32_t* col_idx;         // [heads, cap_per_head]
+  int32_t heads, nqb, stride, cap_per_head;
 };
 
 struct ValidateArgs {
@@ -72,6 +93,7 @@ hipError_t launch_attn_f32(Mode mode, int D, int block_q, AttnArgs a, hipStream_
 hipError_t launch_pool_bf16(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
+hipError_t launch_compact(const CompactArgs& a, hipStream_t s);
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);
 hipError_t launch_window_index(const WindowArgs& a, hipStream_t s);
 // Key blocks [first, last] that the window of query block I touches (shared by host sizing and the kernel).

@@ -50,26 +50,26 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int hk = h / (a.Hq / a.Hkv);
 
   const __bf16* qbase = static_cast<const __bf16*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
-  const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh;
+  const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh + (int64_t)a.key_begin * a.k.sl;
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFrag<D, 1> qf;
   qf.load(qbase, row0, a.L, a.q.sl, lane);
   // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
   const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
-  float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.nkb;
+  float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride + a.out_col0;
   const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
-  const int last_blk = (a.L - 1) / kTileK;
-  const int tail_keys = a.L - last_blk * kTileK;  // keys that exist in the last key block
+  const int last_blk = (a.key_len - 1) / kTileK;
+  const int tail_keys = a.key_len - last_blk * kTileK;  // keys that exist in the last key block of the range
   auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
   TileDma<D, NT, false> kdma;
   kdma.init(a.k.sl, wave, lane);
   KFragAddr<D> kaddr;
   kaddr.init(lane);
-  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(a.L - 1) * a.k.sl + D) * 2);
+  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(a.key_len - 1) * a.k.sl + D) * 2);
   const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2);
-  const int n = a.nkb;
+  const int n = last_blk + 1;
   const float c = a.scale_log2;
 
   auto copy_k_any = [&](int blk, char* dst) {  // a tile that may be the partial last block
@@ -171,23 +171,23 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
   const int hk = h / (a.Hq / a.Hkv);
 
   const float* qbase = static_cast<const float*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
-  const float* kbase = static_cast<const float*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh;
+  const float* kbase = static_cast<const float*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh + (int64_t)a.key_begin * a.k.sl;
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFragF32<D> qf;
   qf.load(qbase, row0, a.L, a.q.sl, lane);
   // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
   const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
-  float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.nkb;
+  float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride + a.out_col0;
   const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
   const int g = lane >> 5;
 
   const int tiles_per_block = a.block_k / kTileKF;
-  const int n_tiles = (a.L + kTileKF - 1) / kTileKF;
+  const int n_tiles = (a.key_len + kTileKF - 1) / kTileKF;
   const float c = a.scale_log2;
   float acc = 0.f;  // thread 0: running sum of the current key block
   for (int t = 0; t < n_tiles; ++t) {
-    const int valid = a.L - t * kTileKF < kTileKF ? a.L - t * kTileKF : kTileKF;  // keys of this tile that exist (>= 1)
+    const int valid = a.key_len - t * kTileKF < kTileKF ? a.key_len - t * kTileKF : kTileKF;  // keys of this tile that exist (>= 1)
     __syncthreads();
     T::template stage<NT>(kbase + (int64_t)t * kTileKF * a.k.sl, a.k.sl, klds, T::kKStride, tid, valid);
     __syncthreads();
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
       for (int w = 0; w < NW; ++w) acc += wsum[w];
       if ((t + 1) % tiles_per_block == 0 || t == n_tiles - 1) {  // key block complete (the last one may be partial)
         const int J = t / tiles_per_block;
-        const int keys_here = a.L - J * a.block_k < a.block_k ? a.L - J * a.block_k : a.block_k;
+        const int keys_here = a.key_len - J * a.block_k < a.block_k ? a.key_len - J * a.block_k : a.block_k;
         arow[J] = acc * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
         acc = 0.f;
       }
@@ -265,10 +265,32 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
   if (r >= a.rows) return;
   const int bh = r / a.nqb, I = r % a.nqb;
   const uint32_t* src = reinterpret_cast<const uint32_t*>(a.apool) + (int64_t)r * a.nkb;
+  const int keep = a.keep_lo + a.keep_hi;
+  if (a.straddle >= 0) {
+    // The ranked row has nkb + 1 entries: blocks before the one that holds the boundary, that block's
+    // prefill part, its generation part, the blocks after it. `split` counts entries of this row.
+    const int Js = a.straddle, nv = a.nkb + 1;
+    const uint32_t* part = reinterpret_cast<const uint32_t*>(a.part) + (int64_t)r * 2;
+    for (int v = lane; v < nv; v += 64) row[v] = v < Js ? src[v] : v == Js ? part[0] : v == Js + 1 ? part[1] : src[v - 1];
+    __syncthreads();
+    int32_t* sel = reinterpret_cast<int32_t*>(row + nv);  // the kept entries of both ranges, still in LDS
+    emit_topk_range(row, 0, a.split, a.keep_lo, sel, lane);
+    emit_topk_range(row, a.split, nv, a.keep_hi, sel + a.keep_lo, lane);
+    __syncthreads();
+    // entries -> key blocks; the only possible duplicate is the boundary block, at the junction of the two ranges
+    const bool dup = a.keep_lo > 0 && a.keep_hi > 0 && sel[a.keep_lo - 1] == Js && sel[a.keep_lo] == Js + 1;
+    int32_t* tmp = a.rows_tmp + (int64_t)r * keep;
+    for (int t = lane; t < keep; t += 64) {
+      if (dup && t == a.keep_lo) continue;
+      const int v = sel[t];
+      tmp[t - ((dup && t > a.keep_lo) ? 1 : 0)] = v > Js ? v - 1 : v;
+    }
+    if (lane == 0) a.counts[r] = keep - (dup ? 1 : 0);
+    return;
+  }
   for (int J = lane; J < a.nkb; J += 64) row[J] = src[J];
   __syncthreads();
 
-  const int keep = a.keep_lo + a.keep_hi;
   int32_t* out = a.col_idx + (int64_t)bh * a.cap_per_head + (int64_t)I * keep;
   emit_topk_range(row, 0, a.split, a.keep_lo, out, lane);
   emit_topk_range(row, a.split, a.nkb, a.keep_hi, out + a.keep_lo, lane);
@@ -277,6 +299,36 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
     rp[I] = I * keep;
     if (I == a.nqb - 1) rp[a.nqb] = a.nqb * keep;
   }
+}
+
+// One work-group per head: exclusive scan of the row lengths, then every row copied to its place.
+__global__ __launch_bounds__(256) void compact_kernel(const CompactArgs a) {
+  __shared__ int32_t partial[256];
+  const int head = blockIdx.x, tid = threadIdx.x;
+  const int per = (a.nqb + 255) / 256;  // consecutive rows per thread
+  const int first = tid * per, last = first + per < a.nqb ? first + per : a.nqb;
+  const int32_t* counts = a.counts + (int64_t)head * a.nqb;
+  int sum = 0;
+  for (int I = first; I < last; ++I) sum += counts[I];
+  partial[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {  // inclusive scan of the per-thread sums
+    const int add = tid >= off ? partial[tid - off] : 0;
+    __syncthreads();
+    partial[tid] += add;
+    __syncthreads();
+  }
+  int offset = partial[tid] - sum;
+  int32_t* rp = a.row_ptr + (int64_t)head * (a.nqb + 1);
+  int32_t* ci = a.col_idx + (int64_t)head * a.cap_per_head;
+  for (int I = first; I < last; ++I) {
+    const int n = counts[I];
+    const int32_t* src = a.rows_tmp + ((int64_t)head * a.nqb + I) * a.stride;
+    rp[I] = offset;
+    for (int t = 0; t < n; ++t) ci[offset + t] = src[t];
+    offset += n;
+  }
+  if (tid == 255) rp[a.nqb] = partial[255];
 }
 
 // ---------------------------------------------------------------------------- index validation
@@ -366,7 +418,8 @@ hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s)
 
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s) {
   if (a.rows <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.rows), dim3(64), (size_t)a.nkb * sizeof(uint32_t), s, a);
+  const size_t lds = a.straddle >= 0 ? (size_t)(a.nkb + 1 + a.keep_lo + a.keep_hi) * sizeof(uint32_t) : (size_t)a.nkb * sizeof(uint32_t);
+  hipLaunchKernelGGL(topk_kernel, dim3((unsigned)a.rows), dim3(64), lds, s, a);
   return hipGetLastError();
 }
 
@@ -374,6 +427,12 @@ hipError_t launch_window_index(const WindowArgs& a, hipStream_t s) {
   const int rows = a.heads * a.nqb;
   if (rows <= 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(window_index_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(const CompactArgs& a, hipStream_t s) {
+  if (a.heads <= 0 || a.nqb <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)a.heads), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

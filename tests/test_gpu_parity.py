@@ -317,6 +317,54 @@ def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_
     assert (guard[:, :, L:] == 7.0).all(), "rows past L were written"
 
 
+@pytest.mark.parametrize("dtype,bq,bk,L,D,ptok,rho", [
+    (torch.bfloat16, 128, 64, 1024, 128, 200, 0.3),    # boundary inside key block 3: 8 prefill keys, 56 generation keys
+    (torch.bfloat16, 64, 64, 1000, 128, 990, 0.25),    # inside the partial last block
+    (torch.bfloat16, 32, 64, 512, 64, 1, 0.4),         # a single prefill key
+    (torch.bfloat16, 128, 64, 1024, 128, 1023, 0.3),   # a single generation key
+    (torch.float32, 32, 32, 256, 64, 50, 0.3),
+    (torch.float32, 64, 64, 300, 64, 70, 0.4),         # 64-key blocks over 32-key tiles, partial last block
+])
+def test_isolated_selection_with_the_boundary_inside_a_block(dtype, bq, bk, L, D, ptok, rho):
+    _say(f"isolated selection, token boundary: {dtype} {bq}x{bk} L={L} p={ptok}")
+    H = 3
+    q, k, v = _rand_qkv(1, H, H, L, D, dtype, seed=L + ptok, scale=1.0 if dtype == torch.float32 and D == 64 else 0.6)
+    qd, kd, vd = _dev(q, k, v)
+    ix = sd.select_pattern_isolated_tokens(qd, kd, bq, bk, rho, ptok)
+    sd.index_validate(ix)
+    rp_o, ci_o, ap, n_pre, vblock = oracle.select_isolated_tokens(q, k, bq, bk, rho, ptok)
+    nv = ap.shape[-1]
+    keep_pre, keep_gen = oracle.kept_blocks(rho, n_pre), oracle.kept_blocks(rho, nv - n_pre)
+    rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+    nqb = -(-L // bq)
+    ties = short_rows = 0
+    for h in range(H):
+        assert rp[0, h, 0] == 0
+        for I in range(nqb):
+            got = ci[0, h, rp[0, h, I]:rp[0, h, I + 1]].tolist()
+            want = ci_o[0, h, rp_o[0, h, I]:rp_o[0, h, I + 1]].tolist()
+            assert got == sorted(set(got))
+            short_rows += len(got) == keep_pre + keep_gen - 1
+            if got == want:
+                continue
+            # a difference is legal only between entries whose oracle score ties with the cut of their range
+            a = ap[0, h, I]
+            cut_pre = np.sort(a[:n_pre])[::-1][keep_pre - 1]
+            cut_gen = np.sort(a[n_pre:])[::-1][keep_gen - 1]
+            for J in set(got) ^ set(want):
+                ok = any((abs(a[e] - (cut_pre if e < n_pre else cut_gen)) <= 1e-5 * (cut_pre if e < n_pre else cut_gen))
+                         for e in range(nv) if vblock[e] == J)
+                assert ok, f"head {h} row {I}: block {J} differs outside the tie band"
+            ties += 1
+    _say(f"   rows={H * nqb} keep={keep_pre}+{keep_gen} rows_with_the_boundary_block_kept_twice={short_rows} tie_rows={ties}")
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    assert_output_close(got, oracle.attn_sparse(q, k, v, rp, ci, bq, bk), dtype, "sparse on the token-boundary pattern")
+    # on a block edge the token form is the block form
+    edge = sd.select_pattern_isolated_tokens(qd, kd, bq, bk, rho, 2 * bk)
+    blk = sd.select_pattern_isolated(qd, kd, bq, bk, rho, 2)
+    assert torch.equal(edge.row_ptr, blk.row_ptr) and torch.equal(edge.col_idx, blk.col_idx)
+
+
 def test_window_index_ragged_length():
     from oracle import patterns
     for L, bq, bk, window, sink in [(1000, 128, 64, 256, 70), (333, 32, 32, 50, 0)]:
