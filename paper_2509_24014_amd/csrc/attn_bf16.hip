@@ -100,9 +100,11 @@ __global__ __launch_bounds__(NW * 64)
   // order, which would force every fragment read issued meanwhile to be waited for in full.
   int opaque_zero;
   asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
+  // Tiles past the end of the list repeat the last one: the steady loop prefetches up to two tiles
+  // ahead without asking whether they exist, and a repeated copy of a real tile into a free buffer is harmless.
   auto col_at = [&](int t) -> int {
-    if (MODE != Mode::kSparse) return t;
     const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
+    if (MODE != Mode::kSparse) return idx;
     return cols[idx + opaque_zero];
   };
   int blk0 = col_at(0), blk1 = col_at(1), blk2 = col_at(2), blk3 = col_at(3);
@@ -118,16 +120,19 @@ __global__ __launch_bounds__(NW * 64)
   auto copy_k = [&](int blk, char* dst) { kdma.issue(krsrc, uni(blk) * k_tile_bytes, dst, wave); };
   auto copy_v = [&](int blk, char* dst) { vdma.issue(vrsrc, uni(blk) * v_tile_bytes, dst, wave); };
   // the same for a tile that may be the partial last block (prologue and the last few tiles only)
-  auto copy_k_any = [&](int blk, char* dst) {
+  // (`ln` is the lane number; the tail loop passes a copy the compiler cannot see through, so that the
+  // per-lane addresses of a partial copy are worked out there and not carried across the steady loop.)
+  auto copy_k_any = [&](int blk, char* dst, int ln) {
     const int ub = uni(blk);
-    if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
+    if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, ln, a.k.sl, tail_keys);
     else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
   };
-  auto copy_v_any = [&](int blk, char* dst) {
+  auto copy_v_any = [&](int blk, char* dst, int ln) {
     const int ub = uni(blk);
-    if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
+    if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, ln, a.v.sl, tail_keys);
     else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
   };
+  int lane_tail = lane;
 
   const float c = a.scale_log2;
 
@@ -197,7 +202,7 @@ __global__ __launch_bounds__(NW * 64)
   // kbuf[P] (held K(t)) and vbuf[1-P] (held V(t-1)) are free and receive K(t+2) and V(t+1).
   //   sub-step 2t+1:  S(2t+2) = K(t+1)[0:32] Q^T,   O += P(2t)   V(t)[0:32],   softmax(2t+1) -> p_odd
   //   sub-step 2t+2:  S(2t+3) = K(t+1)[32:64] Q^T,  O += P(2t+1) V(t)[32:64],  softmax(2t+2) -> p_even
-  // STEADY: t + 2 < n, every piece exists and each sub-step is one branch-free block.
+  // STEADY: tile t+1 exists (t+2 may be a repeat of the last tile) and each sub-step is one branch-free block.
 #define SPARSED_TILE_STEP(P, STEADY, T)                                                            \
   {                                                                                                \
     char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
@@ -210,8 +215,8 @@ __global__ __launch_bounds__(NW * 64)
       copy_k(blk2, kb_free);                                                                       \
       if (kHasV) copy_v(blk1, vb_free);                                                            \
     } else {                                                                                       \
-      if (has_k2) copy_k_any(blk2, kb_free);                                                       \
-      if (kHasV && has_next) copy_v_any(blk1, vb_free);                                            \
+      if (has_k2) copy_k_any(blk2, kb_free, lane_tail);                                            \
+      if (kHasV && has_next) copy_v_any(blk1, vb_free, lane_tail);                                 \
     }                                                                                              \
     const int valid_odd = (STEADY) ? 32 : keys_of(uni(blk0)) - 32;                                 \
     const int valid_even = (STEADY) ? 32 : keys_of(uni(blk1));                                     \
@@ -240,9 +245,9 @@ __global__ __launch_bounds__(NW * 64)
 
   if (n > 0) {
     // prologue: K(0), K(1), V(0) into LDS; S(0); then sub-step 0: S(1) alongside softmax(0)
-    copy_k_any(blk0, kbuf0);
-    if (n > 1) copy_k_any(blk1, kbuf1);
-    if (kHasV) copy_v_any(blk0, vbuf0);
+    copy_k_any(blk0, kbuf0, lane);
+    if (n > 1) copy_k_any(blk1, kbuf1, lane);
+    if (kHasV) copy_v_any(blk0, vbuf0, lane);
     __syncthreads();
     logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
     logits_sub<D, NQ, true>(kbuf0, 1, kaddr, qf, s_odd);
@@ -253,14 +258,17 @@ __global__ __launch_bounds__(NW * 64)
     }
     __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
-    // the steady loop never touches the partial last block: one more tile is left to the tail loop
-    const int steady_reach = 3 + (tail_keys < kTileK ? 1 : 0);
+    // A steady step at tile t needs tile t+1 (its logits are computed there) and prefetches K(t+2), which may
+    // be a repeat. It must never see a partial last block (whose copy and masks live in the tail loop only):
+    // then the last tile has to stay out of reach of the prefetch, two tiles further back.
+    const int steady_reach = (tail_keys < kTileK) ? 4 : 2;
     int t = 0;
     while (t + steady_reach < n) {
       SPARSED_TILE_STEP(0, true, t);
       SPARSED_TILE_STEP(1, true, t + 1);
       t += 2;
     }
+    asm volatile("" : "+v"(lane_tail));
     for (; t < n; ++t) {
       if (t & 1) {
         SPARSED_TILE_STEP(1, false, t);

@@ -110,7 +110,7 @@ void pool_bf16_kernel(const PoolArgs a) {
     char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
     const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
     const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
-    if (STEADY) kdma.issue(krsrc, ((T) + 2) * k_tile_bytes, kb_free, wave);                        \
+    if (STEADY) kdma.issue(krsrc, ((T) + 2 < n ? (T) + 2 : n - 1) * k_tile_bytes, kb_free, wave); /* past the end: a harmless repeat */ \
     else if (has_k2) copy_k_any((T) + 2, kb_free);                                                 \
     if (has_next) logits_sub<D, 1, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                      \
     float part = carry + expsum_sub(s_odd, (STEADY) ? 32 : keys_of(T) - 32);                       \
@@ -136,7 +136,8 @@ void pool_bf16_kernel(const PoolArgs a) {
   carry = expsum_sub(s_even, keys_of(0));
   __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
-  const int steady_reach = 3 + (tail_keys < kTileK ? 1 : 0);  // the steady loop never touches a partial last block
+  // a steady step at tile t needs tile t+1 and prefetches K(t+2) (or a repeat); it never touches a partial last block
+  const int steady_reach = (tail_keys < kTileK) ? 4 : 2;
   int t = 0;
   while (t + steady_reach < n) {
     SPARSED_POOL_STEP(0, true, t);
