@@ -113,6 +113,8 @@ __global__ __launch_bounds__(NW * 64)
   QFrag<D, NQ> qf;
   qf.load(qbase, row0, a.L, a.q.sl, lane);
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
+  // keys that exist in tile number `tile` of the list (block `blk`): none past the end of the list
+  auto keys_at = [&](int tile, int blk) -> int { return tile < n ? keys_of(uni(blk)) : 0; };
   const int64_t slab_rows = (int64_t)(a.L - 1);
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
   const __amdgpu_buffer_rsrc_t vrsrc = make_rsrc(kHasV ? vbase : kbase, kHasV ? (slab_rows * a.v.sl + D) * 2 : 0);
@@ -138,12 +140,13 @@ __global__ __launch_bounds__(NW * 64)
 
   // Online softmax of one 32-key sub-tile: s (fp32 logits) -> p (bf16), updates M / lsum, reports the
   // factor by which the output accumulator has to be rescaled (1 unless the reference maximum moved).
-  // `valid`: keys of this sub-tile that exist (32 or more = all; only the partial last block has fewer).
-  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise, int valid) {
+  // masked: apply `valid`, the number of keys of this sub-tile that exist (32 or more = all, 0 or less =
+  // none: a phantom tile or the empty half of a partial last block). Unmasked steps skip the 16 selects.
+  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise, const bool masked, int valid) {
     any_raise = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      if (valid < 32) {
+      if (masked) {
         // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the sub-tile
         const int mine = valid - 8 * g;
 #pragma unroll
@@ -202,40 +205,39 @@ __global__ __launch_bounds__(NW * 64)
   // kbuf[P] (held K(t)) and vbuf[1-P] (held V(t-1)) are free and receive K(t+2) and V(t+1).
   //   sub-step 2t+1:  S(2t+2) = K(t+1)[0:32] Q^T,   O += P(2t)   V(t)[0:32],   softmax(2t+1) -> p_odd
   //   sub-step 2t+2:  S(2t+3) = K(t+1)[32:64] Q^T,  O += P(2t+1) V(t)[32:64],  softmax(2t+2) -> p_even
-  // STEADY: tile t+1 exists (t+2 may be a repeat of the last tile) and each sub-step is one branch-free block.
-#define SPARSED_TILE_STEP(P, STEADY, T)                                                            \
+  // Tiles past the end of the list are phantoms: their copy repeats the last real tile and all their
+  // keys are masked, so they add nothing, and the same branch-free step serves the whole list. MASKED
+  // steps (the last few of a list) count the keys that exist in each sub-tile and use the copy that
+  // knows about a partial last block; the others assume full, real tiles.
+#define SPARSED_TILE_STEP(P, MASKED, T)                                                            \
   {                                                                                                \
     char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
     char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
     char* const vb_this = (P) ? vbuf1 : vbuf0;                                                     \
     char* const vb_free = (P) ? vbuf0 : vbuf1;                                                     \
-    const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
-    const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
-    if (STEADY) {                                                                                  \
+    if (MASKED) {                                                                                  \
+      copy_k_any(blk2, kb_free, lane_tail);                                                        \
+      if (kHasV) copy_v_any(blk1, vb_free, lane_tail);                                             \
+    } else {                                                                                       \
       copy_k(blk2, kb_free);                                                                       \
       if (kHasV) copy_v(blk1, vb_free);                                                            \
-    } else {                                                                                       \
-      if (has_k2) copy_k_any(blk2, kb_free, lane_tail);                                            \
-      if (kHasV && has_next) copy_v_any(blk1, vb_free, lane_tail);                                 \
     }                                                                                              \
-    const int valid_odd = (STEADY) ? 32 : keys_of(uni(blk0)) - 32;                                 \
-    const int valid_even = (STEADY) ? 32 : keys_of(uni(blk1));                                     \
+    const int valid_odd = (MASKED) ? keys_at((T), blk0) - 32 : 32;                                 \
+    const int valid_even = (MASKED) ? keys_at((T) + 1, blk1) : 32;                                 \
     const int blk_new = col_at((T) + 4);                                                           \
     float alpha[NQ];                                                                               \
     bool any_raise;                                                                                \
-    if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                     \
-    if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 0, vaddr, p_even, o);                             \
-    softmax_sub(s_odd, p_odd, alpha, any_raise, valid_odd);                                        \
-    if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                          \
+    logits_sub<D, NQ, false>(kb_next, 0, kaddr, qf, s_even);                                       \
+    if (kHasV) pv_sub<D, NQ, false>(vb_this, 0, vaddr, p_even, o);                                 \
+    softmax_sub(s_odd, p_odd, alpha, any_raise, (MASKED), valid_odd);                              \
+    sched_substep_interleave<D, NQ, kHasV>();                                                      \
     if (kHasV && any_raise) rescale_output(alpha);                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                             \
-    if (has_next) logits_sub<D, NQ, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                      \
-    if (kHasV) pv_sub<D, NQ, !(STEADY)>(vb_this, 1, vaddr, p_odd, o);                              \
-    if (has_next) {                                                                                \
-      softmax_sub(s_even, p_even, alpha, any_raise, valid_even);                                   \
-      if (STEADY) sched_substep_interleave<D, NQ, kHasV>();                                        \
-      if (kHasV && any_raise) rescale_output(alpha);                                               \
-    }                                                                                              \
+    logits_sub<D, NQ, false>(kb_next, 1, kaddr, qf, s_odd);                                        \
+    if (kHasV) pv_sub<D, NQ, false>(vb_this, 1, vaddr, p_odd, o);                                  \
+    softmax_sub(s_even, p_even, alpha, any_raise, (MASKED), valid_even);                           \
+    sched_substep_interleave<D, NQ, kHasV>();                                                      \
+    if (kHasV && any_raise) rescale_output(alpha);                                                 \
     blk0 = blk1;                                                                                   \
     blk1 = blk2;                                                                                   \
     blk2 = blk3;                                                                                   \
@@ -244,9 +246,9 @@ __global__ __launch_bounds__(NW * 64)
   }
 
   if (n > 0) {
-    // prologue: K(0), K(1), V(0) into LDS; S(0); then sub-step 0: S(1) alongside softmax(0)
+    // prologue: K(0), K(1) (a repeat of K(0) if the list has one tile), V(0) into LDS; S(0); softmax(0)
     copy_k_any(blk0, kbuf0, lane);
-    if (n > 1) copy_k_any(blk1, kbuf1, lane);
+    copy_k_any(blk1, kbuf1, lane);
     if (kHasV) copy_v_any(blk0, vbuf0, lane);
     __syncthreads();
     logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
@@ -254,26 +256,25 @@ __global__ __launch_bounds__(NW * 64)
     {
       float alpha[NQ];
       bool any_raise;
-      softmax_sub(s_even, p_even, alpha, any_raise, keys_of(uni(blk0)));  // O is still zero: nothing to rescale
+      softmax_sub(s_even, p_even, alpha, any_raise, true, keys_at(0, blk0));  // O is still zero: nothing to rescale
     }
     __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
-    // A steady step at tile t needs tile t+1 (its logits are computed there) and prefetches K(t+2), which may
-    // be a repeat. It must never see a partial last block (whose copy and masks live in the tail loop only):
-    // then the last tile has to stay out of reach of the prefetch, two tiles further back.
+    // An unmasked step at tile t touches tiles t, t+1 (softmax) and t+2 (copy, possibly a repeat). A partial
+    // last block must stay out of its reach on all three counts; a full last block only as far as t+1.
     const int steady_reach = (tail_keys < kTileK) ? 4 : 2;
     int t = 0;
     while (t + steady_reach < n) {
-      SPARSED_TILE_STEP(0, true, t);
-      SPARSED_TILE_STEP(1, true, t + 1);
+      SPARSED_TILE_STEP(0, false, t);
+      SPARSED_TILE_STEP(1, false, t + 1);
       t += 2;
     }
     asm volatile("" : "+v"(lane_tail));
     for (; t < n; ++t) {
       if (t & 1) {
-        SPARSED_TILE_STEP(1, false, t);
+        SPARSED_TILE_STEP(1, true, t);
       } else {
-        SPARSED_TILE_STEP(0, false, t);
+        SPARSED_TILE_STEP(0, true, t);
       }
     }
   }

@@ -72,15 +72,18 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int n = last_blk + 1;
   const float c = a.scale_log2;
 
-  auto copy_k_any = [&](int blk, char* dst) {  // a tile that may be the partial last block
+  auto copy_k_any = [&](int tile, char* dst) {  // any tile: past the end repeats the last one, which may be partial
+    const int blk = tile < n ? tile : n - 1;
     if (blk == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, blk * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
     else kdma.issue(krsrc, blk * k_tile_bytes, dst, wave);
   };
+  auto keys_at = [&](int tile) -> int { return tile < n ? keys_of(tile) : 0; };  // keys that exist in a tile (none in a phantom)
   f32x16 s_even[1], s_odd[1];
   float carry = 0.f;  // per-lane sum of the even sub-tile of the key block in progress
   const int g = lane >> 5;
-  auto expsum_sub = [&](f32x16(&s)[1], int valid) -> float {  // valid: keys of the sub-tile that exist (>= 32: all)
-    if (valid < 32) {
+  // masked: apply `valid`, the number of keys of the sub-tile that exist (>= 32: all, <= 0: none)
+  auto expsum_sub = [&](f32x16(&s)[1], const bool masked, int valid) -> float {
+    if (masked) {
       const int mine = valid - 8 * g;  // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8
 #pragma unroll
       for (int x = 0; x < 16; ++x)
@@ -104,51 +107,50 @@ void pool_bf16_kernel(const PoolArgs a) {
 
   // Tile step t (LDS parity P = t & 1) = sub-steps 2t+1 and 2t+2. On entry S(2t+1) is in s_odd, the
   // per-lane sum of sub-tile 2t in `carry`, K(t+1) in kbuf[1-P]; kbuf[P] is free and receives K(t+2).
-#define SPARSED_POOL_STEP(P, STEADY, T)                                                            \
+  // Tiles past the end of the range are phantoms (a repeated copy, every key masked), so one branch-free
+  // step serves the whole range; MASKED steps (the last few) count the keys that exist in each sub-tile.
+#define SPARSED_POOL_STEP(P, MASKED, T)                                                            \
   {                                                                                                \
     char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
     char* const kb_next = (P) ? kbuf0 : kbuf1;                                                     \
-    const bool has_k2 = (STEADY) || ((T) + 2 < n);                                                 \
-    const bool has_next = (STEADY) || ((T) + 1 < n);                                               \
-    if (STEADY) kdma.issue(krsrc, ((T) + 2 < n ? (T) + 2 : n - 1) * k_tile_bytes, kb_free, wave); /* past the end: a harmless repeat */ \
-    else if (has_k2) copy_k_any((T) + 2, kb_free);                                                 \
-    if (has_next) logits_sub<D, 1, !(STEADY)>(kb_next, 0, kaddr, qf, s_even);                      \
-    float part = carry + expsum_sub(s_odd, (STEADY) ? 32 : keys_of(T) - 32);                       \
-    if (STEADY) sched_substep_interleave<D, 1, false>();                                           \
+    if (MASKED) copy_k_any((T) + 2, kb_free);                                                      \
+    else kdma.issue(krsrc, ((T) + 2 < n ? (T) + 2 : n - 1) * k_tile_bytes, kb_free, wave);         \
+    logits_sub<D, 1, false>(kb_next, 0, kaddr, qf, s_even);                                        \
+    float part = carry + expsum_sub(s_odd, (MASKED), keys_at(T) - 32);                             \
+    sched_substep_interleave<D, 1, false>();                                                       \
     part = wave_sum_to_last_lane(part);                                                            \
     if (lane == 63) wsum[(P)][wave] = part;                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                             \
-    if (has_next) {                                                                                \
-      logits_sub<D, 1, !(STEADY)>(kb_next, 1, kaddr, qf, s_odd);                                   \
-      carry = expsum_sub(s_even, (STEADY) ? 32 : keys_of((T) + 1));                                \
-      if (STEADY) sched_substep_interleave<D, 1, false>();                                         \
-    }                                                                                              \
+    logits_sub<D, 1, false>(kb_next, 1, kaddr, qf, s_odd);                                         \
+    carry = expsum_sub(s_even, (MASKED), keys_at((T) + 1));                                        \
+    sched_substep_interleave<D, 1, false>();                                                       \
     __syncthreads();                                                                               \
     flush_block((T), part);                                                                        \
   }
 
-  // prologue: K(0), K(1) into LDS; S(0); then sub-step 0: S(1) alongside the sums of sub-tile 0
+  // prologue: K(0), K(1) (a repeat of K(0) for a one-tile range) into LDS; S(0); the sums of sub-tile 0
   copy_k_any(0, kbuf0);
-  if (n > 1) copy_k_any(1, kbuf1);
+  copy_k_any(1, kbuf1);
   __syncthreads();
   logits_sub<D, 1, true>(kbuf0, 0, kaddr, qf, s_even);
   logits_sub<D, 1, true>(kbuf0, 1, kaddr, qf, s_odd);
-  carry = expsum_sub(s_even, keys_of(0));
+  carry = expsum_sub(s_even, true, keys_at(0));
   __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
-  // a steady step at tile t needs tile t+1 and prefetches K(t+2) (or a repeat); it never touches a partial last block
+  // an unmasked step at tile t touches tiles t, t+1 (sums) and t+2 (copy, possibly a repeat); a partial last
+  // block must stay out of its reach on all three counts, a full one only as far as t+1
   const int steady_reach = (tail_keys < kTileK) ? 4 : 2;
   int t = 0;
   while (t + steady_reach < n) {
-    SPARSED_POOL_STEP(0, true, t);
-    SPARSED_POOL_STEP(1, true, t + 1);
+    SPARSED_POOL_STEP(0, false, t);
+    SPARSED_POOL_STEP(1, false, t + 1);
     t += 2;
   }
   for (; t < n; ++t) {
     if (t & 1) {
-      SPARSED_POOL_STEP(1, false, t);
+      SPARSED_POOL_STEP(1, true, t);
     } else {
-      SPARSED_POOL_STEP(0, false, t);
+      SPARSED_POOL_STEP(0, true, t);
     }
   }
 #undef SPARSED_POOL_STEP
