@@ -383,6 +383,48 @@ def test_window_index_ragged_length():
         assert np.array_equal(ix.col_idx.cpu().numpy().reshape(2, -1)[:, :col.shape[1]], col)
 
 
+# ----------------------------------------------------------------------------- seeded sweep over the parameter space
+def _sweep_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+        D = int(rng.choice([64, 128]))
+        bq = int(rng.choice([32, 64, 128]))
+        bk = 64 if dtype == torch.bfloat16 else int(rng.choice([32, 64]))
+        Hkv = int(rng.choice([1, 2]))
+        Hq = Hkv * int(rng.choice([1, 2, 3]))
+        B = int(rng.choice([1, 2]))
+        L = int(rng.integers(1, 700 if dtype == torch.bfloat16 else 300))
+        rho = float(rng.choice([0.05, 0.2, 0.5, 1.0]))
+        cases.append((i, dtype, B, Hq, Hkv, L, D, bq, bk, rho))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(24, seed=2024), ids=lambda c: f"{c[0]}-{str(c[1])[6:]}-B{c[2]}H{c[3]}/{c[4]}-L{c[5]}-D{c[6]}-{c[7]}x{c[8]}-rho{c[9]}")
+def test_sweep_dense_select_sparse(case):
+    """Every entry point on shapes drawn at random (seeded): any length from 1 up, both head dims, all block
+    shapes, grouped heads, batch 1-2. Dense, selection (index inside the tie band) and sparse on the GPU's index."""
+    i, dtype, B, Hq, Hkv, L, D, bq, bk, rho = case
+    _say(f"sweep {case}")
+    q, k, v = _rand_qkv(B, Hq, Hkv, L, D, dtype, seed=100 + i, scale=1.0 if dtype == torch.float32 and D == 64 else 0.5)
+    qd, kd, vd = _dev(q, k, v)
+    assert_output_close(sd.attn_dense(qd, kd, vd), oracle.attn_dense(q, k, v), dtype, "sweep dense")
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    pooled = torch.empty(B, Hq, nqb, nkb, dtype=torch.float32, device=DEV)
+    ix = sd.select_pattern(qd, kd, bq, bk, rho, pooled_out=pooled)
+    sd.index_validate(ix)
+    row_ptr, col_idx, apool, _ = oracle.select_pattern(q, k, bq, bk, rho)
+    keep = oracle.kept_blocks(rho, nkb)
+    assert np.array_equal(ix.row_ptr.cpu().numpy(), row_ptr)
+    rel = np.abs(pooled.cpu().double().numpy() - apool) / apool
+    assert rel.max() < 5e-6, f"pooled scores off by {rel.max():.2e}"
+    compare_index(ix.col_idx.cpu().numpy()[..., :nqb * keep], col_idx, apool.reshape(-1, nkb), keep)
+    got = sd.attn_sparse(qd, kd, vd, ix)
+    want = oracle.attn_sparse(q, k, v, ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy(), bq, bk)
+    assert_output_close(got, want, dtype, "sweep sparse")
+
+
 # ----------------------------------------------------------------------------- fixed patterns (Section 4.1 baselines)
 @pytest.mark.parametrize("L,bq,bk,window,sink", [
     (1024, 128, 64, 256, 0),      # sliding window
