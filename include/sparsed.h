@@ -93,7 +93,21 @@ typedef struct sparsed_exec {
   float* lse_out;         /* attn_dense: optional [B, Hq, L] fp32, log-sum-exp of each row's scaled logits */
   const float* lse_in;    /* select_pattern: optional [B, Hq, L] fp32 from attn_dense on the SAME q, k */
   float* pooled_out;      /* select_pattern: optional [B, Hq, nqb, nkb] fp32 copy of the pooled scores A' */
+  const int32_t* seq_lens; /* optional DEVICE array [B]: per-sample lengths, see below */
 } sparsed_exec;
+
+/*
+ * Per-sample lengths (not in the paper, whose runs use one length per call): with ex->seq_lens set,
+ * batch element b has min(seq_lens[b], L) tokens; its rows and keys at or past that do not exist.
+ *  - attn_dense / attn_sparse: those query rows are neither computed nor stored (out and lse_out keep
+ *    what they held); keys past the length are masked.
+ *  - select_pattern: sample b pools and ranks its own ceil(len / block_k) key blocks and keeps
+ *    sparsed_kept_blocks(rho, that many) per query block: row_ptr[I] = I * k_b for its ceil(len / block_q)
+ *    query blocks, and the query blocks it does not have get empty rows. pooled_out entries of blocks a
+ *    sample does not have are not written. nqb, nkb and cap_per_head are still those of L.
+ *  - A length <= 0 makes the whole sample a no-op. The isolated-selection entry points do not take
+ *    per-sample lengths (SPARSED_ERR_UNSUPPORTED).
+ */
 
 /*
  * Full attention of the early denoising steps (Section 3.1, Eq. 1; Algorithm 1,

@@ -48,7 +48,8 @@ class _BlockIndex(ctypes.Structure):
 
 class _Exec(ctypes.Structure):
     _fields_ = [("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("lse_out", ctypes.c_void_p), ("lse_in", ctypes.c_void_p), ("pooled_out", ctypes.c_void_p)]
+                ("lse_out", ctypes.c_void_p), ("lse_in", ctypes.c_void_p), ("pooled_out", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p)]
 
 
 _lib = None
@@ -175,12 +176,22 @@ def select_workspace_bytes(q: torch.Tensor, block_q: int, block_k: int) -> int:
     return int(load_library().sparsed_select_workspace_bytes(ctypes.byref(t), block_q, block_k))
 
 
-def attn_dense(q, k, v, out: Optional[torch.Tensor] = None, lse_out: Optional[torch.Tensor] = None, stream=None):
+def _seq_lens_ptr(seq_lens, B):
+    if seq_lens is None:
+        return None
+    if seq_lens.dtype != torch.int32 or not seq_lens.is_cuda or not seq_lens.is_contiguous() or seq_lens.numel() != B:
+        raise ValueError("seq_lens must be a contiguous int32 device tensor [B]")
+    return seq_lens.data_ptr()
+
+
+def attn_dense(q, k, v, out: Optional[torch.Tensor] = None, lse_out: Optional[torch.Tensor] = None, stream=None,
+               seq_lens: Optional[torch.Tensor] = None):
     """sparsed_attn_dense: full bidirectional attention (Eq. 1). Returns ``out``."""
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
-    ex = _Exec(_stream_ptr(stream), None, 0, lse_out.data_ptr() if lse_out is not None else None, None, None)
+    ex = _Exec(_stream_ptr(stream), None, 0, lse_out.data_ptr() if lse_out is not None else None, None, None,
+               _seq_lens_ptr(seq_lens, q.shape[0]))
     if lse_out is not None and (lse_out.dtype != torch.float32 or not lse_out.is_contiguous()
                                 or lse_out.numel() != q.shape[0] * q.shape[1] * q.shape[2]):
         raise ValueError("lse_out must be contiguous fp32 [B, Hq, L]")
@@ -189,7 +200,8 @@ def attn_dense(q, k, v, out: Optional[torch.Tensor] = None, lse_out: Optional[to
     return out
 
 
-def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pooled_out, index, stream, prefill_tokens=None):
+def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pooled_out, index, stream, prefill_tokens=None,
+            seq_lens=None):
     lib = load_library()
     B, H, L, D = q.shape
     nqb, nkb = -(-L // block_q), -(-L // block_k)
@@ -213,7 +225,8 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
     if lse_in is not None and (lse_in.dtype != torch.float32 or not lse_in.is_contiguous() or lse_in.numel() != B * H * L):
         raise ValueError("lse_in must be contiguous fp32 [B, Hq, L]")
     ex = _Exec(_stream_ptr(stream), workspace.data_ptr(), workspace.numel() * workspace.element_size(), None,
-               lse_in.data_ptr() if lse_in is not None else None, pooled_out.data_ptr() if pooled_out is not None else None)
+               lse_in.data_ptr() if lse_in is not None else None, pooled_out.data_ptr() if pooled_out is not None else None,
+               _seq_lens_ptr(seq_lens, B))
     tq, tk, ci = _tensor(q, "q"), _tensor(k, "k"), index._c()
     if prefill_tokens is not None:
         st = lib.sparsed_select_pattern_isolated_tokens(ctypes.byref(tq), ctypes.byref(tk), block_q, block_k, float(rho),
@@ -229,9 +242,9 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
 
 
 def select_pattern(q, k, block_q: int, block_k: int, rho: float, lse_in=None, workspace=None, pooled_out=None,
-                   index: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
+                   index: Optional[BlockIndex] = None, stream=None, seq_lens: Optional[torch.Tensor] = None) -> BlockIndex:
     """sparsed_select_pattern: pooled post-softmax scores + per-row top-k -> CSR block index."""
-    return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream)
+    return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, seq_lens=seq_lens)
 
 
 def select_pattern_isolated(q, k, block_q: int, block_k: int, rho: float, prefill_blocks: int, lse_in=None, workspace=None,
@@ -246,12 +259,13 @@ def select_pattern_isolated_tokens(q, k, block_q: int, block_k: int, rho: float,
     return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, prefill_tokens=int(prefill_tokens))
 
 
-def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, stream=None):
+def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, stream=None,
+                seq_lens: Optional[torch.Tensor] = None):
     """sparsed_attn_sparse: block-sparse attention with a stored pattern (Eq. 3, Eq. 4). Returns ``out``."""
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
-    ex = _Exec(_stream_ptr(stream), None, 0, None, None, None)
+    ex = _Exec(_stream_ptr(stream), None, 0, None, None, None, _seq_lens_ptr(seq_lens, q.shape[0]))
     tq, tk, tv, to, ci = _tensor(q, "q"), _tensor(k, "k"), _tensor(v, "v"), _tensor(out, "out"), index._c()
     _check(lib.sparsed_attn_sparse(ctypes.byref(tq), ctypes.byref(tk), ctypes.byref(tv), ctypes.byref(ci), ctypes.byref(to),
                                    ctypes.byref(ex)))

@@ -150,6 +150,7 @@ sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tenso
   a.Hq = q->H;
   a.Hkv = k->H;
   a.L = q->L;
+  a.seq_lens = ex ? ex->seq_lens : nullptr;
   a.scale_log2 = scale_log2(q->D);
   int block_q = 0;
   if (mode == Mode::kSparse) {
@@ -180,6 +181,8 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   if ((st = check_index_shape(ix, q))) return st;
   if (ix->block_q != bq || ix->block_k != bk) return fail(SPARSED_ERR_INDEX, "block index blocks %dx%d differ from %dx%d", ix->block_q, ix->block_k, bq, bk);
   const int nqb = ix->nqb, nkb = ix->nkb;
+  const int32_t* seq_lens = ex ? ex->seq_lens : nullptr;
+  if (seq_lens && isolated) return fail(SPARSED_ERR_UNSUPPORTED, "isolated selection does not take per-sample lengths");
   if (nkb > 8192) return fail(SPARSED_ERR_UNSUPPORTED, "more than 8192 key blocks per row (%d)", nkb);
   int split = nkb, keep_lo, keep_hi = 0;
   const int straddle = boundary_token >= 0 ? boundary_token / bk : -1;  // the key block that holds the boundary
@@ -228,6 +231,7 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
     a.Hq = q->H;
     a.Hkv = k->H;
     a.L = q->L;
+    a.seq_lens = seq_lens;
     a.scale_log2 = scale_log2(q->D);
     const hipError_t e = bf16 ? launch_attn_bf16(Mode::kStats, q->D, 0, a, s) : launch_attn_f32(Mode::kStats, q->D, 0, a, s);
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
@@ -243,6 +247,7 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   p.Hq = q->H;
   p.Hkv = k->H;
   p.L = q->L;
+  p.seq_lens = seq_lens;
   p.nqb = nqb;
   p.block_k = bk;
   p.key_begin = 0;
@@ -287,6 +292,12 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   t.keep_lo = keep_lo;
   t.keep_hi = keep_hi;
   t.cap_per_head = ix->cap_per_head;
+  t.seq_lens = seq_lens;
+  t.heads_per_batch = q->H;
+  t.block_q = bq;
+  t.block_k = bk;
+  t.L = q->L;
+  t.rho = rho;
   t.straddle = straddle;
   t.part = part;
   t.rows_tmp = rows_tmp;

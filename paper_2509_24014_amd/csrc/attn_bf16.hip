@@ -48,6 +48,13 @@ __global__ __launch_bounds__(NW * 64)
   const int bh = lid / a.n_qtiles;
   const int b = bh / a.Hq, h = bh % a.Hq;
   const int hk = h / (a.Hq / a.Hkv);
+  // length of this batch element: the tensor's L unless the caller passed per-sample lengths
+  int L = a.L;
+  if (a.seq_lens != nullptr) {
+    const int len = a.seq_lens[b];
+    L = len < a.L ? len : a.L;
+  }
+  if (qt * QT >= L) return;  // a query tile wholly past the end (uniform over the work-group)
 
   const __bf16* qbase = static_cast<const __bf16*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
   const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh;
@@ -63,12 +70,12 @@ __global__ __launch_bounds__(NW * 64)
     n = end - beg;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
-    n = (a.L + kTileK - 1) / kTileK;
+    n = (L + kTileK - 1) / kTileK;
   }
   // A sequence length that is not a multiple of the tile leaves the last key block partial: its
   // missing keys are masked to -inf in the softmax and its missing rows never fetched.
-  const int last_blk = (a.L - 1) / kTileK;
-  const int tail_keys = a.L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
+  const int last_blk = (L - 1) / kTileK;
+  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
   auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
   float M[NQ], lsum[NQ];
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(NW * 64)
   // Q after the block numbers: the loads complete in issue order, so the first K/V copies (which
   // need blk0, blk1) can start while the Q rows are still on their way.
   QFrag<D, NQ> qf;
-  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  qf.load(qbase, row0, L, a.q.sl, lane);
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
   // keys that exist in tile number `tile` of the list (block `blk`): none past the end of the list
   auto keys_at = [&](int tile, int blk) -> int { return tile < n ? keys_of(uni(blk)) : 0; };
@@ -292,7 +299,7 @@ __global__ __launch_bounds__(NW * 64)
   for (int nq = 0; nq < NQ; ++nq) {
     const float ltot = pair_sum(lsum[nq]);
     const int row = row0 + nq * 32 + j;
-    if (a.lse != nullptr && g == 0 && row < a.L)
+    if (a.lse != nullptr && g == 0 && row < L)
       a.lse[(int64_t)bh * a.L + row] = (M[nq] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
     if (kHasV) {
       const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(NW * 64)
         const int r = it * kRowsPerStore + lane / kSlots, slot = lane % kSlots;
         const u32x4 w = *reinterpret_cast<const u32x4*>(stage + r * kRowBytes + ((slot ^ (r & (kSlots - 1))) << 4));
         const int grow = row0 + nq * 32 + r;
-        if (grow < a.L) *reinterpret_cast<u32x4*>(obase + (int64_t)grow * a.o_sl + slot * 8) = w;  // partial last query tile: rows past L are dropped
+        if (grow < L) *reinterpret_cast<u32x4*>(obase + (int64_t)grow * a.o_sl + slot * 8) = w;  // partial last query tile: rows past L are dropped
       }
     }
   }

@@ -26,6 +26,12 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
   const int bh = lid / a.n_qtiles;
   const int b = bh / a.Hq, h = bh % a.Hq;
   const int hk = h / (a.Hq / a.Hkv);
+  int L = a.L;  // length of this batch element
+  if (a.seq_lens != nullptr) {
+    const int len = a.seq_lens[b];
+    L = len < a.L ? len : a.L;
+  }
+  if (qt * QT >= L) return;  // a query tile wholly past the end (uniform over the work-group)
 
   const float* qbase = static_cast<const float*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
   const float* kbase = static_cast<const float*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh;
@@ -41,11 +47,11 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
     n_tiles = (end - beg) * tiles_per_block;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
-    n_tiles = (a.L + kTileKF - 1) / kTileKF;
+    n_tiles = (L + kTileKF - 1) / kTileKF;
   }
 
   QFragF32<D> qf;
-  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  qf.load(qbase, row0, L, a.q.sl, lane);
 
   float M = -1e30f, lsum = 0.f;
   f32x16 o[D / 32];
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
     }
     // keys of this tile that exist: fewer than 32 only at the end of a sequence whose length is not a
     // multiple of the tile; a tile wholly past the end (second half of a partial 64-key block) is skipped
-    const int valid = a.L - key0 < kTileKF ? a.L - key0 : kTileKF;
+    const int valid = L - key0 < kTileKF ? L - key0 : kTileKF;
     if (valid <= 0) continue;  // uniform over the work-group
     __syncthreads();  // everyone is done reading the previous tile
     T::template stage<NT>(kbase + (int64_t)key0 * a.k.sl, a.k.sl, klds, T::kKStride, tid, valid);
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
 
   const float ltot = lsum + other_half_f(lsum);
   const int row = row0 + j;
-  if (row >= a.L) return;  // partial last query tile
+  if (row >= L) return;  // partial last query tile
   if (a.lse != nullptr && g == 0) a.lse[(int64_t)bh * a.L + row] = (M + log2f(ltot)) * 0.6931471805599453f;
   if (kHasV) {
     const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;

@@ -21,8 +21,9 @@ struct AttnArgs {
   const int32_t* row_ptr;  // sparse only: [B, Hq, nqb + 1]
   const int32_t* col_idx;  // sparse only: [B, Hq, cap_per_head]
   int32_t B, Hq, Hkv, L;
+  const int32_t* seq_lens; // optional [B]: rows and keys of batch element b at or past seq_lens[b] do not exist
   int32_t nqb, cap_per_head, block_k;
-  int32_t n_qtiles;        // query tiles per head = L / (rows per work-group)
+  int32_t n_qtiles;        // query tiles per head = ceil(L / rows per work-group)
   float scale_log2;        // log2(e) / sqrt(D)
 };
 
@@ -34,6 +35,7 @@ struct PoolArgs {
   const float* lse;        // [B, Hq, L] natural-log sum-exp of each row over ALL L keys
   float* apool;            // [B, Hq, nqb, out_stride]; block t of the range lands in column out_col0 + t
   int32_t B, Hq, Hkv, L;
+  const int32_t* seq_lens; // optional [B] per-sample lengths (only with the whole-sequence key range)
   int32_t nqb, block_k;
   int32_t key_begin, key_len;
   int32_t out_stride, out_col0;
@@ -53,6 +55,11 @@ struct TopkArgs {
   // with score part[2r] (its prefill keys) and the second with part[2r+1] (its generation keys); it is
   // listed once even if both keep it, so rows differ in length: entries go to rows_tmp [rows, keep_lo +
   // keep_hi] and counts [rows], and compact_kernel builds the CSR from them.
+  // Per-sample lengths (optional, single range only): sample b ranks its first ceil(len/block_k) entries,
+  // keeps kept_blocks(rho, that many) of them, and its query blocks past ceil(len/block_q) get empty rows.
+  const int32_t* seq_lens;
+  int32_t heads_per_batch, block_q, block_k, L;
+  double rho;
   int32_t straddle;
   const float* part;
   int32_t* rows_tmp;

@@ -49,25 +49,33 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int b = bh / a.Hq, h = bh % a.Hq;
   const int hk = h / (a.Hq / a.Hkv);
 
+  // length of this batch element (per-sample lengths shorten the whole-sequence key range with it)
+  int L = a.L, key_len = a.key_len;
+  if (a.seq_lens != nullptr) {
+    const int len = a.seq_lens[b];
+    L = len < a.L ? len : a.L;
+    key_len = L - a.key_begin < key_len ? L - a.key_begin : key_len;
+  }
+  if (I * (32 * NW) >= L || key_len <= 0) return;  // uniform over the work-group
   const __bf16* qbase = static_cast<const __bf16*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
   const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh + (int64_t)a.key_begin * a.k.sl;
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFrag<D, 1> qf;
-  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  qf.load(qbase, row0, L, a.q.sl, lane);
   // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
-  const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
+  const float lse2 = (row0 + j < L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride + a.out_col0;
-  const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
-  const int last_blk = (a.key_len - 1) / kTileK;
-  const int tail_keys = a.key_len - last_blk * kTileK;  // keys that exist in the last key block of the range
+  const int rows_here = (L - I * (32 * NW) < 32 * NW) ? L - I * (32 * NW) : 32 * NW;  // query rows that exist
+  const int last_blk = (key_len - 1) / kTileK;
+  const int tail_keys = key_len - last_blk * kTileK;  // keys that exist in the last key block of the range
   auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
 
   TileDma<D, NT, false> kdma;
   kdma.init(a.k.sl, wave, lane);
   KFragAddr<D> kaddr;
   kaddr.init(lane);
-  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(a.key_len - 1) * a.k.sl + D) * 2);
+  const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, ((int64_t)(key_len - 1) * a.k.sl + D) * 2);
   const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2);
   const int n = last_blk + 1;
   const float c = a.scale_log2;
@@ -173,24 +181,31 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
   const int b = bh / a.Hq, h = bh % a.Hq;
   const int hk = h / (a.Hq / a.Hkv);
 
+  int L = a.L, key_len = a.key_len;  // length of this batch element
+  if (a.seq_lens != nullptr) {
+    const int len = a.seq_lens[b];
+    L = len < a.L ? len : a.L;
+    key_len = L - a.key_begin < key_len ? L - a.key_begin : key_len;
+  }
+  if (I * (32 * NW) >= L || key_len <= 0) return;  // uniform over the work-group
   const float* qbase = static_cast<const float*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
   const float* kbase = static_cast<const float*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh + (int64_t)a.key_begin * a.k.sl;
   const int row0 = I * (32 * NW) + wave * 32;
 
   QFragF32<D> qf;
-  qf.load(qbase, row0, a.L, a.q.sl, lane);
+  qf.load(qbase, row0, L, a.q.sl, lane);
   // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
-  const float lse2 = (row0 + j < a.L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
+  const float lse2 = (row0 + j < L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride + a.out_col0;
-  const int rows_here = (a.L - I * (32 * NW) < 32 * NW) ? a.L - I * (32 * NW) : 32 * NW;  // query rows that exist
+  const int rows_here = (L - I * (32 * NW) < 32 * NW) ? L - I * (32 * NW) : 32 * NW;  // query rows that exist
   const int g = lane >> 5;
 
   const int tiles_per_block = a.block_k / kTileKF;
-  const int n_tiles = (a.key_len + kTileKF - 1) / kTileKF;
+  const int n_tiles = (key_len + kTileKF - 1) / kTileKF;
   const float c = a.scale_log2;
   float acc = 0.f;  // thread 0: running sum of the current key block
   for (int t = 0; t < n_tiles; ++t) {
-    const int valid = a.key_len - t * kTileKF < kTileKF ? a.key_len - t * kTileKF : kTileKF;  // keys of this tile that exist (>= 1)
+    const int valid = key_len - t * kTileKF < kTileKF ? key_len - t * kTileKF : kTileKF;  // keys of this tile that exist (>= 1)
     __syncthreads();
     T::template stage<NT>(kbase + (int64_t)t * kTileKF * a.k.sl, a.k.sl, klds, T::kKStride, tid, valid);
     __syncthreads();
@@ -211,7 +226,7 @@ __global__ __launch_bounds__(NW * 64) void pool_f32_kernel(const PoolArgs a) {
       for (int w = 0; w < NW; ++w) acc += wsum[w];
       if ((t + 1) % tiles_per_block == 0 || t == n_tiles - 1) {  // key block complete (the last one may be partial)
         const int J = t / tiles_per_block;
-        const int keys_here = a.key_len - J * a.block_k < a.block_k ? a.key_len - J * a.block_k : a.block_k;
+        const int keys_here = key_len - J * a.block_k < a.block_k ? key_len - J * a.block_k : a.block_k;
         arow[J] = acc * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
         acc = 0.f;
       }
@@ -289,6 +304,30 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
       tmp[t - ((dup && t > a.keep_lo) ? 1 : 0)] = v > Js ? v - 1 : v;
     }
     if (lane == 0) a.counts[r] = keep - (dup ? 1 : 0);
+    return;
+  }
+  if (a.seq_lens != nullptr) {
+    // per-sample length: this sample ranks the key blocks it has and keeps its own "top rho%" of them
+    const int len = a.seq_lens[bh / a.heads_per_batch];
+    const int L = len < a.L ? len : a.L;
+    const int nkb_b = L > 0 ? (L + a.block_k - 1) / a.block_k : 0, nqb_b = L > 0 ? (L + a.block_q - 1) / a.block_q : 0;
+    int keep_b = 0;
+    if (nkb_b > 0) {  // the host's count rule, in the same double arithmetic
+      double x = ceil(a.rho * (double)nkb_b - 1e-9);
+      if (!(x >= 1.0)) x = 1.0;
+      if (x > (double)nkb_b) x = (double)nkb_b;
+      keep_b = (int)x;
+    }
+    int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1);
+    if (I < nqb_b) {
+      for (int J = lane; J < nkb_b; J += 64) row[J] = src[J];
+      __syncthreads();
+      emit_topk_range(row, 0, nkb_b, keep_b, a.col_idx + (int64_t)bh * a.cap_per_head + (int64_t)I * keep_b, lane);
+    }
+    if (lane == 0) {
+      rp[I] = (I < nqb_b ? I : nqb_b) * keep_b;  // query blocks the sample does not have get empty rows
+      if (I == a.nqb - 1) rp[a.nqb] = nqb_b * keep_b;
+    }
     return;
   }
   for (int J = lane; J < a.nkb; J += 64) row[J] = src[J];

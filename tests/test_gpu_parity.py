@@ -383,6 +383,49 @@ def test_window_index_ragged_length():
         assert np.array_equal(ix.col_idx.cpu().numpy().reshape(2, -1)[:, :col.shape[1]], col)
 
 
+# ----------------------------------------------------------------------------- per-sample lengths inside one batch
+@pytest.mark.parametrize("dtype,bq,bk,L,D,lens,rho", [
+    (torch.bfloat16, 128, 64, 1024, 128, [1024, 70, 333, 640], 0.25),
+    (torch.bfloat16, 64, 64, 512, 64, [1, 512, 65, 129], 0.3),
+    (torch.float32, 32, 32, 200, 64, [200, 33, 100], 0.4),
+])
+def test_per_sample_lengths(dtype, bq, bk, L, D, lens, rho):
+    """A padded batch with a length per sample: every sample must equal the oracle run on that sample cut to
+    its length, and nothing past a sample's length may be written."""
+    _say(f"per-sample lengths {dtype} {bq}x{bk} L={L} lens={lens}")
+    B, Hq, Hkv = len(lens), 2, 1
+    q, k, v = _rand_qkv(B, Hq, Hkv, L, D, dtype, seed=L + D, scale=1.0 if dtype == torch.float32 and D == 64 else 0.5)
+    qd, kd, vd = _dev(q, k, v)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    out = torch.full((B, Hq, L, D), 7.0, dtype=dtype, device=DEV)
+    lse = torch.full((B, Hq, L), 7.0, dtype=torch.float32, device=DEV)
+    sd.attn_dense(qd, kd, vd, out=out, lse_out=lse, seq_lens=sl)
+    ix = sd.select_pattern(qd, kd, bq, bk, rho, lse_in=lse, seq_lens=sl)
+    ix_own = sd.select_pattern(qd, kd, bq, bk, rho, seq_lens=sl)      # statistics pass of its own
+    sd.index_validate(ix)
+    assert torch.equal(ix.row_ptr, ix_own.row_ptr)
+    out_s = torch.full((B, Hq, L, D), 7.0, dtype=dtype, device=DEV)
+    sd.attn_sparse(qd, kd, vd, ix, out=out_s, seq_lens=sl)
+    torch.cuda.synchronize()
+    rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+    for b, n in enumerate(lens):
+        qb, kb, vb = q[b:b + 1, :, :n], k[b:b + 1, :, :n], v[b:b + 1, :, :n]
+        assert_output_close(out[b:b + 1, :, :n], oracle.attn_dense(qb, kb, vb), dtype, f"dense sample {b}")
+        assert (out[b, :, n:] == 7.0).all() and (lse[b, :, n:] == 7.0).all() and (out_s[b, :, n:] == 7.0).all()
+        rp_o, ci_o, apool, _ = oracle.select_pattern(qb, kb, bq, bk, rho)
+        nqb_b, nkb_b = -(-n // bq), -(-n // bk)
+        keep = oracle.kept_blocks(rho, nkb_b)
+        for h in range(Hq):
+            assert rp[b, h, :nqb_b + 1].tolist() == rp_o[0, h].tolist()
+            assert (rp[b, h, nqb_b:] == nqb_b * keep).all()           # query blocks the sample does not have: empty rows
+            compare_index(ci[b, h, :nqb_b * keep], ci_o[0, h], apool[0, h], keep)
+        # sparse output of this sample against the oracle on the GPU's own rows for it
+        rp_b = rp[b:b + 1, :, :nqb_b + 1].copy()
+        want = oracle.attn_sparse(qb, kb, vb, rp_b, ci[b:b + 1], bq, bk)
+        assert_output_close(out_s[b:b + 1, :, :n], want, dtype, f"sparse sample {b}")
+
+
 # ----------------------------------------------------------------------------- seeded sweep over the parameter space
 def _sweep_cases(n, seed):
     rng = np.random.default_rng(seed)
