@@ -61,3 +61,12 @@ def test_sparse_step_before_selection_is_an_error(recorder):
     q = torch.zeros(1, 1, 64, 64)
     with pytest.raises(RuntimeError):
         layer.step(q, q, q, 3)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
