@@ -144,6 +144,11 @@ struct TileDma {
   // that exists, so every address stays inside the tensor; their logits are masked by the caller.
   __device__ __forceinline__ void issue_partial(__amdgpu_buffer_rsrc_t rsrc, int32_t tile_byte_offset, char* lds_tile,
                                                 int wave_in_group, int lane, int64_t stride_l, int rows) const {
+    // Worked out afresh at every call on purpose (the lane number is made opaque): these few integer
+    // operations run a handful of times per work-group, whereas per-lane offsets hoisted out of the
+    // caller's loop would have to live in registers the main loop has none to spare for.
+    asm volatile("" : "+v"(lane));
+    const int32_t row_bytes = (int32_t)(stride_l * 2);
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       const int wl = wave_in_group * kPerWave + u;
@@ -151,8 +156,7 @@ struct TileDma {
       source_of(wl, lane, &row, &chunk);
       if (row >= rows) row = rows - 1;
       char* dst = lds_tile + lds_piece_offset(wl);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, (int32_t)(row * stride_l * 2 + chunk * 16),
-                                               tile_byte_offset, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, row * row_bytes + chunk * 16, tile_byte_offset, 0, 0);
     }
   }
   // rsrc: buffer descriptor of the (batch, head) slab; tile_byte_offset: wave-uniform byte offset of
