@@ -99,3 +99,43 @@ def test_workspace_size_formula():
     r = _t(B=1, H=2, L=250, D=64)
     assert lib.sparsed_select_workspace_bytes(ctypes.byref(r), 32, 32) == 2048 + 2 * 8 * 8 * 4   # ceil(250/32) = 8 blocks each way
     assert lib.sparsed_select_workspace_bytes(ctypes.byref(t), 0, 64) == 0
+
+
+def test_no_fallback_when_the_library_is_missing(monkeypatch, tmp_path):
+    """Without libsparsed.so (and with nothing to build it from) every entry point must raise: there is no CPU path."""
+    import torch
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libsparsed.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library(build_if_missing=False)
+
+    def no_compiler(force=True, verbose=False):
+        raise RuntimeError("hipcc failed")
+
+    from paper_2509_24014_amd import build as build_mod
+    monkeypatch.setattr(build_mod, "build", no_compiler)
+    x = torch.zeros(1, 1, 64, 64)
+    for call in (lambda: binding.kept_blocks(0.3, 8), lambda: binding.attn_dense(x, x, x)):
+        with pytest.raises((RuntimeError, FileNotFoundError, OSError, ValueError)):
+            call()
+    assert binding._lib is None
+
+
+def test_product_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing under the package or the workload generator may import,
+    link or read it (only tests, the smoke check and the benchmark's CPU baseline do)."""
+    pkg = os.path.join(ROOT, "paper_2509_24014_amd")
+    offenders = []
+    for base in (pkg, os.path.join(ROOT, "workload"), os.path.join(ROOT, "include")):
+        for dirpath, _, files in os.walk(base):
+            for f in files:
+                if f.endswith((".py", ".hip", ".hpp", ".h", ".c", ".cpp")):
+                    text = open(os.path.join(dirpath, f), errors="ignore").read()
+                    if re.search(r"import\s+oracle|from\s+oracle|oracle\.|liboracle|oracle/", text):
+                        offenders.append(os.path.join(dirpath, f))
+    assert offenders == []
+    # and the oracle shares nothing with the product either
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2509_24014_amd" not in text and "sparsed.h" not in text and "csrc" not in text
