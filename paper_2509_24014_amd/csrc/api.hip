@@ -199,6 +199,9 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
     keep_lo = sparsed_kept_blocks(rho, nkb);
   }
   const int keep = keep_lo + keep_hi;
+  // the ranking kernel stages one pooled row (and, with a boundary inside a block, its kept entries) in 64 KB of LDS
+  if (straddle >= 0 && (int64_t)nkb + 1 + keep > 16384)
+    return fail(SPARSED_ERR_UNSUPPORTED, "row of %d key blocks with %d kept entries does not fit the ranking kernel", nkb, keep);
   if ((int64_t)ix->cap_per_head < (int64_t)nqb * keep)
     return fail(SPARSED_ERR_INDEX, "cap_per_head %d < nqb*k = %lld", ix->cap_per_head, (long long)nqb * keep);
 
