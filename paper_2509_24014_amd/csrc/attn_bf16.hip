@@ -360,6 +360,7 @@ hipError_t launch_attn_bf16(Mode mode, int D, int block_q, AttnArgs a, hipStream
   const int qtile = (mode == Mode::kSparse) ? block_q : dense_qtile_bf16(a.L);
   if (qtile == 0) return hipErrorInvalidValue;
   a.n_qtiles = (a.L + qtile - 1) / qtile;
+  if (mode == Mode::kSparse && qtile <= 64) return launch_attn_bf16_splitk(D, qtile, a, s);  // small query blocks
   if (D == 128) {
     if (mode == Mode::kDense) return launch_by_qtile<128, Mode::kDense>(qtile, a, s);
     if (mode == Mode::kSparse) return launch_by_qtile<128, Mode::kSparse>(qtile, a, s);

@@ -97,6 +97,8 @@ enum class Mode : int { kDense = 0, kSparse = 1, kStats = 2 };
 // the sparse and pooled kernels; dense and stats pick their own query tile from L.
 hipError_t launch_attn_bf16(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s);
 hipError_t launch_attn_f32(Mode mode, int D, int block_q, AttnArgs a, hipStream_t s);
+// bf16 sparse attention for query blocks of 32 or 64 rows (two waves per 32 rows, keys of a tile split between them)
+hipError_t launch_attn_bf16_splitk(int D, int block_q, const AttnArgs& a, hipStream_t s);
 hipError_t launch_pool_bf16(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
