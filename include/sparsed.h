@@ -134,7 +134,8 @@ sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor*
  * be >= nqb*k, else SPARSED_ERR_INDEX. Needs a workspace of
  * sparsed_select_workspace_bytes(); if ex or ex->workspace is NULL the library
  * uses a device buffer of its own, allocated (synchronously) on first use and
- * kept for the life of the process.
+ * kept for the life of the process; calls that rely on it must not overlap on one
+ * GPU (they would share it), so callers with several streams pass their own.
  */
 sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_tensor* k,
                                       int32_t block_q, int32_t block_k, double rho,

@@ -18,7 +18,7 @@
 namespace sparsed {
 
 template <int D, int RW>
-__global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_splitk_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 2 ? 2 : 1, RW >= 2 ? 2 : 1))) void attn_bf16_splitk_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NW = 2 * RW, NT = NW * 64, QT = 32 * RW;
   constexpr int kKBytes = KLayout<D>::kTileBytes, kVBytes = VLayout<D>::kTileBytes;

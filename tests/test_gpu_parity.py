@@ -383,6 +383,37 @@ def test_window_index_ragged_length():
         assert np.array_equal(ix.col_idx.cpu().numpy().reshape(2, -1)[:, :col.shape[1]], col)
 
 
+# ----------------------------------------------------------------------------- streams
+def test_calls_run_on_the_callers_stream():
+    """Work is enqueued on the stream passed in (here: torch's current stream inside a stream context), so a chain
+    dense -> select -> sparse on a side stream needs no synchronisation in between and two chains on two
+    streams, each with its own workspace, do not disturb each other."""
+    q, k, v = _rand_qkv(1, 4, 2, 1024, 128, torch.bfloat16, seed=5, scale=0.5)
+    qd, kd, vd = _dev(q, k, v)
+    q2 = (qd.float() * 0.5).to(torch.bfloat16)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    results = []
+    torch.cuda.synchronize()
+    for s, qq in zip(streams, (qd, q2)):
+        with torch.cuda.stream(s):
+            lse = torch.empty(1, 4, 1024, dtype=torch.float32, device=DEV)
+            dense = sd.attn_dense(qq, kd, vd, lse_out=lse)
+            ix = sd.select_pattern(qq, kd, 128, 64, 0.25, lse_in=lse)
+            sparse = sd.attn_sparse(qq, kd, vd, ix)
+            results.append((qq, dense, ix, sparse))
+    for s in streams:
+        s.synchronize()
+    for qq, dense, ix, sparse in results:
+        qc = qq.cpu()
+        assert_output_close(dense, oracle.attn_dense(qc, k, v), torch.bfloat16, "dense on a side stream")
+        want = oracle.attn_sparse(qc, k, v, ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy(), 128, 64)
+        assert_output_close(sparse, want, torch.bfloat16, "sparse on a side stream")
+        ref = sd.select_pattern(qq, kd, 128, 64, 0.25)          # default stream, own statistics
+        assert torch.equal(ref.row_ptr, ix.row_ptr)
+        _, ci_o, apool, _ = oracle.select_pattern(qc, k, 128, 64, 0.25)
+        compare_index(ix.col_idx.cpu().numpy(), ci_o, apool.reshape(-1, 16), oracle.kept_blocks(0.25, 16))
+
+
 # ----------------------------------------------------------------------------- per-sample lengths inside one batch
 @pytest.mark.parametrize("dtype,bq,bk,L,D,lens,rho", [
     (torch.bfloat16, 128, 64, 1024, 128, [1024, 70, 333, 640], 0.25),
