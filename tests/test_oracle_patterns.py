@@ -51,3 +51,18 @@ def test_csr_layout():
     ptr, col = patterns.rows_to_csr(rows, 3)
     assert ptr.shape == (3, 5) and ptr[1].tolist() == [0, 1, 3, 5, 7]
     assert col[2].tolist() == [0, 0, 1, 0, 2, 0, 3]
+
+
+def test_host_capacity_formula_matches_the_token_level_count():
+    """The host-side entry count of the window builder (block arithmetic) against the number of kept blocks
+    of the token-level definition, over a seeded sweep that includes lengths that are not block multiples."""
+    from paper_2509_24014_amd import binding
+    rng = np.random.default_rng(7)
+    for _ in range(60):
+        bq, bk = int(rng.choice([32, 64, 128])), int(rng.choice([32, 64]))
+        L = int(rng.integers(1, 900))
+        window, sink = int(rng.integers(0, 2 * L)), int(rng.integers(0, L + 1))
+        nqb, nkb = -(-L // bq), -(-L // bk)
+        m = patterns.window_token_mask(L, window, sink)
+        total = sum(m[I * bq:(I + 1) * bq, J * bk:(J + 1) * bk].any() for I in range(nqb) for J in range(nkb))
+        assert binding.index_window_entries(L, bq, bk, window, sink) == total, (L, bq, bk, window, sink)
