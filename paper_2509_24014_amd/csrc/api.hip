@@ -424,11 +424,7 @@ sparsed_status sparsed_index_fill_window(sparsed_block_index* ix, int32_t seq_le
   a.half_window = window_tokens / 2;
   a.sink_blocks = (sink_tokens + ix->block_k - 1) / ix->block_k;
   int64_t total = 0;
-  for (int I = 0; I < ix->nqb; ++I) {
-    int first, last;
-    window_block_range(I, a.block_q, a.block_k, a.L, a.half_window, &first, &last);
-    total += (a.sink_blocks < first ? a.sink_blocks : first) + (last - first + 1);
-  }
+  for (int I = 0; I < ix->nqb; ++I) total += window_row_length(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks);
   if (total > ix->cap_per_head) return fail(SPARSED_ERR_INDEX, "cap_per_head %d < %lld entries the pattern needs", ix->cap_per_head, (long long)total);
   const hipError_t e = launch_window_index(a, stream_of(ex));
   if (e != hipSuccess) return hip_fail(e, "window index launch");
@@ -439,11 +435,7 @@ int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t b
   if (seq_len <= 0 || block_q <= 0 || block_k <= 0 || window_tokens < 0 || sink_tokens < 0) return -1;
   const int sink_blocks = (sink_tokens + block_k - 1) / block_k;
   int64_t total = 0;
-  for (int I = 0; I < ceil_div(seq_len, block_q); ++I) {
-    int first, last;
-    window_block_range(I, block_q, block_k, seq_len, window_tokens / 2, &first, &last);
-    total += (sink_blocks < first ? sink_blocks : first) + (last - first + 1);
-  }
+  for (int I = 0; I < ceil_div(seq_len, block_q); ++I) total += window_row_length(I, block_q, block_k, seq_len, window_tokens / 2, sink_blocks);
   return total;
 }
 

@@ -105,13 +105,24 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t s);
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);
 hipError_t launch_window_index(const WindowArgs& a, hipStream_t s);
-// Key blocks [first, last] that the window of query block I touches (shared by host sizing and the kernel).
-__host__ __device__ inline void window_block_range(int I, int block_q, int block_k, int L, int half_window, int* first, int* last) {
+// Row I of the window + sink pattern as two disjoint ascending runs of key blocks: the sink blocks
+// [0, *sink_end) and the window blocks [*first, *last] that are not sinks already (empty if *first > *last).
+// Shared by the host-side sizing and the kernel.
+__host__ __device__ inline void window_row_runs(int I, int block_q, int block_k, int L, int half_window, int sink_blocks,
+                                                int* sink_end, int* first, int* last) {
   long lo = (long)I * block_q - half_window, hi = (long)(I + 1) * block_q - 1 + half_window;
   if (lo < 0) lo = 0;
   if (hi > L - 1) hi = L - 1;
+  const int nkb = (L + block_k - 1) / block_k;
+  *sink_end = sink_blocks < nkb ? sink_blocks : nkb;
   *first = (int)(lo / block_k);
   *last = (int)(hi / block_k);
+  if (*first < *sink_end) *first = *sink_end;
+}
+__host__ __device__ inline int window_row_length(int I, int block_q, int block_k, int L, int half_window, int sink_blocks) {
+  int sink_end, first, last;
+  window_row_runs(I, block_q, block_k, L, half_window, sink_blocks, &sink_end, &first, &last);
+  return sink_end + (last >= first ? last - first + 1 : 0);
 }
 // Matrix-core rate probe: kProbeGroups work-groups x 8 waves, each wave issues 32 MFMAs per iteration.
 constexpr int kProbeGroups = 256;

@@ -401,17 +401,14 @@ __global__ __launch_bounds__(256) void window_index_kernel(const WindowArgs a) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= a.heads * a.nqb) return;
   const int bh = r / a.nqb, I = r % a.nqb;
-  int offset = 0, first = 0, last = 0;
-  for (int i = 0; i <= I; ++i) {
-    window_block_range(i, a.block_q, a.block_k, a.L, a.half_window, &first, &last);
-    const int sinks = a.sink_blocks < first ? a.sink_blocks : first;
-    if (i < I) offset += sinks + (last - first + 1);
-  }
-  const int sinks = a.sink_blocks < first ? a.sink_blocks : first;
+  int offset = 0;
+  for (int i = 0; i < I; ++i) offset += window_row_length(i, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks);
+  int sink_end, first, last;
+  window_row_runs(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks, &sink_end, &first, &last);
   int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1);
   int32_t* ci = a.col_idx + (int64_t)bh * a.cap_per_head + offset;
   int n = 0;
-  for (int J = 0; J < sinks; ++J) ci[n++] = J;
+  for (int J = 0; J < sink_end; ++J) ci[n++] = J;
   for (int J = first; J <= last; ++J) ci[n++] = J;
   rp[I] = offset;
   if (I == a.nqb - 1) rp[a.nqb] = offset + n;

@@ -367,7 +367,7 @@ def test_isolated_selection_with_the_boundary_inside_a_block(dtype, bq, bk, L, D
 
 def test_window_index_ragged_length():
     from oracle import patterns
-    for L, bq, bk, window, sink in [(1000, 128, 64, 256, 70), (333, 32, 32, 50, 0)]:
+    for L, bq, bk, window, sink in [(1000, 128, 64, 256, 70), (333, 32, 32, 50, 0), (821, 32, 64, 8, 410)]:
         # the token-level definition on the padded grid, cut back to the L real tokens
         nqb, nkb = -(-L // bq), -(-L // bk)
         m = patterns.window_token_mask(L, window, sink)
@@ -507,6 +507,8 @@ def test_sweep_dense_select_sparse(case):
     (512, 64, 64, 0, 0),          # diagonal only
     (512, 64, 64, 4096, 0),       # window wider than the sequence: every block
     (2048, 64, 32, 300, 33),      # fp32 block shape, many rows
+    (1024, 128, 64, 64, 410),     # sinks reach past the window of the first rows: the two runs merge
+    (1024, 32, 64, 8, 1024),      # every key is a sink
 ])
 def test_window_index_matches_token_level_definition(L, bq, bk, window, sink):
     from oracle import patterns
