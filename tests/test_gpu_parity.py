@@ -499,6 +499,94 @@ def test_sweep_dense_select_sparse(case):
     assert_output_close(got, want, dtype, "sweep sparse")
 
 
+def test_sweep_window_index_builder():
+    from oracle import patterns
+    rng = np.random.default_rng(11)
+    for _ in range(16):
+        bq, bk = int(rng.choice([32, 64, 128])), int(rng.choice([32, 64]))
+        L = int(rng.integers(1, 1500))
+        window, sink = int(rng.integers(0, 2 * L)), int(rng.integers(0, L + 1))
+        H = int(rng.integers(1, 4))
+        nqb, nkb = -(-L // bq), -(-L // bk)
+        m = patterns.window_token_mask(L, window, sink)
+        rows = [np.array([J for J in range(nkb) if m[I * bq:(I + 1) * bq, J * bk:(J + 1) * bk].any()], dtype=np.int32) for I in range(nqb)]
+        ptr, col = patterns.rows_to_csr(rows, H)
+        ix = sd.index_fill_window(1, H, L, bq, bk, window, sink, DEV)
+        sd.index_validate(ix)
+        assert np.array_equal(ix.row_ptr.cpu().numpy().reshape(H, -1), ptr), (L, bq, bk, window, sink)
+        assert np.array_equal(ix.col_idx.cpu().numpy().reshape(H, -1)[:, :col.shape[1]], col), (L, bq, bk, window, sink)
+
+
+def _rows_equal_within_ties(got_rows, want_rows, score_rows, cut_of):
+    """got/want: lists of block lists; a difference is legal only for blocks whose score ties with the cut."""
+    ties = 0
+    for r, (g, w) in enumerate(zip(got_rows, want_rows)):
+        assert list(g) == sorted(set(g))
+        if list(g) == list(w):
+            continue
+        for J in set(g) ^ set(w):
+            sc, cut = score_rows[r](J), cut_of[r](J)
+            assert any(abs(a - c) <= 1e-5 * abs(c) for a, c in zip(sc, cut)), f"row {r}: block {J} differs outside the tie band"
+        ties += 1
+    return ties
+
+
+def test_sweep_isolated_selection_blocks_and_tokens():
+    rng = np.random.default_rng(12)
+    for it in range(10):
+        dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+        bq = int(rng.choice([32, 64, 128]))
+        bk = 64 if dtype == torch.bfloat16 else int(rng.choice([32, 64]))
+        D = int(rng.choice([64, 128]))
+        L = int(rng.integers(bk + 1, 700 if dtype == torch.bfloat16 else 300))
+        rho = float(rng.choice([0.1, 0.3, 0.6]))
+        ptok = int(rng.integers(0, L + 1))
+        H = 2
+        _say(f"isolated sweep {it}: {dtype} {bq}x{bk} L={L} D={D} rho={rho} p={ptok}")
+        q, k, _ = _rand_qkv(1, H, 1, L, D, dtype, seed=300 + it, scale=1.0 if dtype == torch.float32 and D == 64 else 0.6)
+        qd, kd = _dev(q, k)
+        nqb, nkb = -(-L // bq), -(-L // bk)
+        # boundary in tokens
+        ix = sd.select_pattern_isolated_tokens(qd, kd, bq, bk, rho, ptok)
+        sd.index_validate(ix)
+        rp_o, ci_o, ap, n_pre, vblock = oracle.select_isolated_tokens(q, k, bq, bk, rho, ptok)
+        nv = ap.shape[-1]
+        kp, kg = (oracle.kept_blocks(rho, n_pre) if n_pre else 0), (oracle.kept_blocks(rho, nv - n_pre) if nv > n_pre else 0)
+        rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+        for h in range(H):
+            got = [ci[0, h, rp[0, h, I]:rp[0, h, I + 1]].tolist() for I in range(nqb)]
+            want = [ci_o[0, h, rp_o[0, h, I]:rp_o[0, h, I + 1]].tolist() for I in range(nqb)]
+
+            def scores(I):
+                return lambda J: [ap[0, h, I, e] for e in range(nv) if vblock[e] == J]
+
+            def cuts(I):
+                a = ap[0, h, I]
+                cp = np.sort(a[:n_pre])[::-1][kp - 1] if kp else np.nan
+                cg = np.sort(a[n_pre:])[::-1][kg - 1] if kg else np.nan
+                return lambda J: [cp if e < n_pre else cg for e in range(nv) if vblock[e] == J]
+            _rows_equal_within_ties(got, want, [scores(I) for I in range(nqb)], [cuts(I) for I in range(nqb)])
+        # boundary in blocks
+        pb = int(rng.integers(0, nkb + 1))
+        ixb = sd.select_pattern_isolated(qd, kd, bq, bk, rho, pb)
+        sd.index_validate(ixb)
+        apool = oracle.pool_scores(q, k, bq, bk)
+        rpb, cib = oracle.select_isolated(apool, rho, pb)
+        keep = (oracle.kept_blocks(rho, pb) if pb else 0) + (oracle.kept_blocks(rho, nkb - pb) if nkb > pb else 0)
+        assert np.array_equal(ixb.row_ptr.cpu().numpy(), rpb)
+        gotb = ixb.col_idx.cpu().numpy()[..., :nqb * keep].reshape(-1, keep)
+        wantb = cib.reshape(-1, keep)
+        a2 = apool.reshape(-1, nkb)
+        for r in range(gotb.shape[0]):
+            if list(gotb[r]) == list(wantb[r]):
+                continue
+            cp = np.sort(a2[r, :pb])[::-1][oracle.kept_blocks(rho, pb) - 1] if pb else np.nan
+            cg = np.sort(a2[r, pb:])[::-1][oracle.kept_blocks(rho, nkb - pb) - 1] if nkb > pb else np.nan
+            for J in set(gotb[r]) ^ set(wantb[r]):
+                cut = cp if J < pb else cg
+                assert abs(a2[r, J] - cut) <= 1e-5 * abs(cut), f"block form, row {r}, block {J}"
+
+
 # ----------------------------------------------------------------------------- fixed patterns (Section 4.1 baselines)
 @pytest.mark.parametrize("L,bq,bk,window,sink", [
     (1024, 128, 64, 256, 0),      # sliding window
