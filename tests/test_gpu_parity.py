@@ -383,6 +383,28 @@ def test_window_index_ragged_length():
         assert np.array_equal(ix.col_idx.cpu().numpy().reshape(2, -1)[:, :col.shape[1]], col)
 
 
+# ----------------------------------------------------------------------------- strided views through every entry point
+@pytest.mark.parametrize("dtype,L,bq,bk,D", [(torch.bfloat16, 1000, 128, 64, 128), (torch.bfloat16, 333, 64, 64, 64), (torch.float32, 200, 32, 32, 64)])
+def test_packed_qkv_views_through_select_and_sparse(dtype, L, bq, bk, D):
+    """Q, K, V as views of one packed projection output [B, L, 3, H, D] (row stride 3*H*D, head stride D):
+    nothing is copied, every kernel sees strided rows, including the partial last tile."""
+    B, H = 2, 3
+    g = torch.Generator().manual_seed(L)
+    packed = (torch.randn(B, L, 3, H, D, generator=g) * 0.6).to(dtype)
+    pd = packed.to(DEV)
+    q, k, v = (packed[:, :, i].permute(0, 2, 1, 3) for i in range(3))          # [B, H, L, D] views on the host
+    qd, kd, vd = (pd[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    assert not qd.is_contiguous() and qd.stride(2) == 3 * H * D
+    dense = sd.attn_dense(qd, kd, vd)
+    assert_output_close(dense, oracle.attn_dense(q, k, v), dtype, "dense on packed views")
+    ix = _check_selection(q, k, bq, bk, 0.3, False, "select on packed views")   # helper copies q, k to the device contiguously
+    ixv = sd.select_pattern(qd, kd, bq, bk, 0.3)                                 # the same call on the strided views
+    assert torch.equal(ix.row_ptr, ixv.row_ptr) and torch.equal(ix.col_idx, ixv.col_idx)
+    got = sd.attn_sparse(qd, kd, vd, ixv)
+    want = oracle.attn_sparse(q, k, v, ixv.row_ptr.cpu().numpy(), ixv.col_idx.cpu().numpy(), bq, bk)
+    assert_output_close(got, want, dtype, "sparse on packed views")
+
+
 # ----------------------------------------------------------------------------- streams
 def test_calls_run_on_the_callers_stream():
     """Work is enqueued on the stream passed in (here: torch's current stream inside a stream context), so a chain
