@@ -114,7 +114,13 @@ __global__ __launch_bounds__(NW * 64)
     if (MODE != Mode::kSparse) return idx;
     return cols[idx + opaque_zero];
   };
-  int blk0 = col_at(0), blk1 = col_at(1), blk2 = col_at(2), blk3 = col_at(3);
+  int blk0 = 0, blk1 = 0, blk2 = 0, blk3 = 0;
+  if (n > 0) {  // a query block that kept nothing has no list entry to read
+    blk0 = col_at(0);
+    blk1 = col_at(1);
+    blk2 = col_at(2);
+    blk3 = col_at(3);
+  }
   // Q after the block numbers: the loads complete in issue order, so the first K/V copies (which
   // need blk0, blk1) can start while the Q rows are still on their way.
   QFrag<D, NQ> qf;
