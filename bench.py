@@ -92,6 +92,46 @@ def cpu_baseline(cfg, q, k, v, index, keep, budget_s=15.0):
     return out
 
 
+def _sclk_while(fn, seconds=2.5):
+    """Shader clock in MHz as `rocm-smi --showclocks` reports it while fn() runs back to back; None if unreadable.
+
+    The published matrix peak assumes 2400 MHz; under its power limit the chip runs these kernels slower.
+    """
+    import re
+    import shutil
+    import subprocess
+    import threading
+    import torch
+    smi = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    stop = threading.Event()
+    dev = torch.cuda.current_device()
+
+    def work():
+        torch.cuda.set_device(dev)
+        while not stop.is_set():
+            fn()
+            torch.cuda.synchronize()
+
+    th = threading.Thread(target=work, daemon=True)
+    th.start()
+    vals = []
+    try:
+        time.sleep(0.7)
+        t0 = time.time()
+        while time.time() - t0 < seconds:
+            out = subprocess.run([smi, "--showclocks"], capture_output=True, text=True, timeout=15).stdout
+            m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", out)
+            if not m:
+                break
+            vals.append(int(m.group(1)))
+    except Exception:
+        pass
+    finally:
+        stop.set()
+        th.join()
+    return round(sum(vals) / len(vals)) if vals else None
+
+
 def _select_bytes(cfg, keep):
     """Algorithmic bytes of one selection call that reuses the dense call's statistics."""
     esz = 2 if cfg.dtype == "bf16" else 4
@@ -110,6 +150,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-schedule", action="store_true", help="skip the full T-step schedule run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clock", action="store_true", help="do not sample the shader clock under load")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE runs")
     args = ap.parse_args()
@@ -260,6 +301,11 @@ def main():
                                         "kernel": "bf16 32x32x16 matrix instructions only, operands in registers"}
         for key, val in (("roofline", sparse_tf), ("roofline_dense", dense_tf), ("roofline_select", select_tf)):
             result[key]["frac_of_measured_rate_random_operands"] = val / rand_tf
+    under_profiler = "rocprof" in os.environ.get("LD_PRELOAD", "") or any(key.startswith("ROCPROF") for key in os.environ)
+    if not args.no_clock and not under_profiler:
+        result["shader_clock_mhz"] = {"at_published_peak": 2400,
+                                      "during_attn_dense": _sclk_while(lambda: sd.attn_dense(q, k, v, out=out)),
+                                      "during_attn_sparse": _sclk_while(lambda: sd.attn_sparse(q, k, v, index, out=out))}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, index, keep)
     print(json.dumps(result))
