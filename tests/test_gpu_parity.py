@@ -824,6 +824,10 @@ def test_workload_long64k_sampled():
     _check_workload_sampled("long64k", n_per_type=3)
 
 
+def test_twice_the_papers_longest_context_sampled():
+    _check_workload_sampled("probe128k", n_per_type=2)
+
+
 def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     """bench.py on the small 4k workload: one JSON line on stdout carrying every field its readers rely on."""
     import json
