@@ -14,7 +14,10 @@
  *    returns. Descriptor structs themselves live in HOST memory.
  *  - Work is enqueued on `ex->stream` (a hipStream_t; NULL or ex == NULL means
  *    the default stream) and the call returns without synchronising, except
- *    where a function says it synchronises.
+ *    where a function says it synchronises. sparsed_attn_dense,
+ *    sparsed_attn_sparse and, given a workspace, the selection entry points
+ *    only launch kernels (no allocation, no memset, no copy), so they may be
+ *    recorded into a HIP graph on a capturing stream.
  *  - Errors are returned as a sparsed_status; nothing throws or aborts. On any
  *    status other than SPARSED_OK no kernel was launched and outputs are
  *    untouched. sparsed_last_error() gives a thread-local message.

@@ -851,3 +851,50 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and "traffic" in roof
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
+
+
+def test_hot_path_replays_from_a_hip_graph():
+    """dense (with row statistics) -> select -> sparse are kernel launches only when the caller brings the workspace
+    and the index, so the three calls can be captured once into a HIP graph. Replays on new contents of the same
+    buffers, with eager work and synchronisation between them, equal the eager calls bit for bit every time."""
+    B, H, L, D, bq, bk, rho = 1, 4, 1024, 128, 64, 64, 0.25
+    nqb, nkb = L // bq, L // bk
+    keep = sd.kept_blocks(rho, nkb)
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    q, k, v = (torch.randn(B, H, L, D, device=DEV, generator=gen).to(torch.bfloat16) for _ in range(3))
+    lse = torch.empty(B, H, L, dtype=torch.float32, device=DEV)
+    out_d, out_s = torch.empty_like(q), torch.empty_like(q)
+    index = sd.BlockIndex(torch.empty(B, H, nqb + 1, dtype=torch.int32, device=DEV),
+                          torch.empty(B, H, nqb * keep, dtype=torch.int32, device=DEV), bq, bk, nkb)
+    ws = torch.empty(sd.select_workspace_bytes(q, bq, bk), dtype=torch.uint8, device=DEV)
+
+    def hot_path():
+        sd.attn_dense(q, k, v, out=out_d, lse_out=lse)
+        sd.select_pattern(q, k, bq, bk, rho, lse_in=lse, workspace=ws, index=index)
+        sd.attn_sparse(q, k, v, index, out=out_s)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        hot_path()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        hot_path()
+    for trial in range(4):
+        for t in (q, k, v):
+            t.copy_(torch.randn(B, H, L, D, device=DEV, generator=gen).to(torch.bfloat16))
+        for t in (out_d, out_s, lse):
+            t.fill_(float("nan"))
+        index.col_idx.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        lse_e = torch.empty_like(lse)
+        dense_e = sd.attn_dense(q, k, v, lse_out=lse_e)
+        index_e = sd.select_pattern(q, k, bq, bk, rho, lse_in=lse_e)
+        sparse_e = sd.attn_sparse(q, k, v, index_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_d, dense_e) and torch.equal(lse, lse_e), f"replay {trial}: dense"
+        assert torch.equal(index.row_ptr, index_e.row_ptr) and torch.equal(index.col_idx, index_e.col_idx), f"replay {trial}: index"
+        assert torch.equal(out_s, sparse_e), f"replay {trial}: sparse"
