@@ -18,8 +18,9 @@ def window_token_mask(L, window_tokens, sink_tokens):
 def window_block_rows(L, bq, bk, window_tokens, sink_tokens):
     """List of ascending key-block lists, one per query block."""
     m = window_token_mask(L, window_tokens, sink_tokens)
-    blocks = m.reshape(L // bq, bq, L // bk, bk).any(axis=(1, 3))
-    return [np.nonzero(row)[0].astype(np.int32) for row in blocks]
+    nqb, nkb = -(-L // bq), -(-L // bk)  # the last block of either axis may be partial
+    return [np.array([J for J in range(nkb) if m[I * bq:(I + 1) * bq, J * bk:(J + 1) * bk].any()], dtype=np.int32)
+            for I in range(nqb)]
 
 
 def rows_to_csr(rows, heads):

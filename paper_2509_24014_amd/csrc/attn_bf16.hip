@@ -62,21 +62,24 @@ __global__ __launch_bounds__(NW * 64)
   const int row0 = qt * QT + wave * (32 * NQ);  // first query row of this wave
 
   // key tiles to visit
+  // A listed key block of 128 keys is two consecutive 64-key tiles of the list.
+  const int tile_shift = (MODE == Mode::kSparse && a.block_k == 2 * kTileK) ? 1 : 0;
   int n;
   const int32_t* cols = nullptr;
   if (MODE == Mode::kSparse) {
     const int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1) + qt;
     const int beg = rp[0], end = rp[1];
-    n = end - beg;
+    n = (end - beg) << tile_shift;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
     n = (L + kTileK - 1) / kTileK;
   }
-  // A sequence length that is not a multiple of the tile leaves the last key block partial: its
-  // missing keys are masked to -inf in the softmax and its missing rows never fetched.
-  const int last_blk = (L - 1) / kTileK;
-  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
-  auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
+  // A sequence length that is not a multiple of the tile leaves the last key tile partial: its
+  // missing keys are masked to -inf in the softmax and its missing rows never fetched. The second tile
+  // of a partial 128-key block may lie wholly past the end: no keys, every logit masked.
+  const int last_blk = (L - 1) / kTileK;        // last key TILE that exists
+  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in it
+  auto keys_of = [&](int blk) -> int { return blk > last_blk ? 0 : blk == last_blk ? tail_keys : kTileK; };
 
   float M[NQ], lsum[NQ];
   f32x16 o[NQ][D / 32];
@@ -109,10 +112,10 @@ __global__ __launch_bounds__(NW * 64)
   asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
   // Tiles past the end of the list repeat the last one: the steady loop prefetches up to two tiles
   // ahead without asking whether they exist, and a repeated copy of a real tile into a free buffer is harmless.
-  auto col_at = [&](int t) -> int {
+  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list
     const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
     if (MODE != Mode::kSparse) return idx;
-    return cols[idx + opaque_zero];
+    return (cols[(idx >> tile_shift) + opaque_zero] << tile_shift) + (idx & tile_shift);
   };
   int blk0 = 0, blk1 = 0, blk2 = 0, blk3 = 0;
   if (n > 0) {  // a query block that kept nothing has no list entry to read
@@ -138,12 +141,12 @@ __global__ __launch_bounds__(NW * 64)
   // (`ln` is the lane number; the tail loop passes a copy the compiler cannot see through, so that the
   // per-lane addresses of a partial copy are worked out there and not carried across the steady loop.)
   auto copy_k_any = [&](int blk, char* dst, int ln) {
-    const int ub = uni(blk);
+    const int ub = uni(blk) < last_blk ? uni(blk) : last_blk;  // a tile past the end: any real tile will do
     if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, ln, a.k.sl, tail_keys);
     else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
   };
   auto copy_v_any = [&](int blk, char* dst, int ln) {
-    const int ub = uni(blk);
+    const int ub = uni(blk) < last_blk ? uni(blk) : last_blk;
     if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, ln, a.v.sl, tail_keys);
     else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
   };
@@ -275,7 +278,8 @@ __global__ __launch_bounds__(NW * 64)
 
     // An unmasked step at tile t touches tiles t, t+1 (softmax) and t+2 (copy, possibly a repeat). A partial
     // last block must stay out of its reach on all three counts; a full last block only as far as t+1.
-    const int steady_reach = (tail_keys < kTileK) ? 4 : 2;
+    // (with 128-key blocks the last block's second tile may not exist at all: same treatment)
+    const int steady_reach = (tail_keys < kTileK || (tile_shift && !(last_blk & 1))) ? 4 : 2;
     int t = 0;
     while (t + steady_reach < n) {
       SPARSED_TILE_STEP(0, false, t);

@@ -52,10 +52,11 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
 
   const int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1) + qt;
   const int beg = rp[0], end = rp[1];
-  const int n = end - beg;
+  const int tile_shift = a.block_k == 2 * kTileK ? 1 : 0;  // a listed 128-key block is two consecutive tiles
+  const int n = (end - beg) << tile_shift;
   const int32_t* cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
-  const int last_blk = (L - 1) / kTileK;
-  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in the last key block
+  const int last_blk = (L - 1) / kTileK;        // last key TILE that exists
+  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in it
 
   float M = -1e30f, lsum = 0.f;
   f32x16 o[1][D / 32];
@@ -78,7 +79,10 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
   // block numbers of tiles t .. t+3, read with a vector load (see attn_bf16.hip); past the end: the last one
   int opaque_zero;
   asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
-  auto col_at = [&](int t) -> int { return cols[(t < n ? t : (n > 0 ? n - 1 : 0)) + opaque_zero]; };
+  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list
+    const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
+    return (cols[(idx >> tile_shift) + opaque_zero] << tile_shift) + (idx & tile_shift);
+  };
   int blk0 = 0, blk1 = 0, blk2 = 0, blk3 = 0;
   if (n > 0) {
     blk0 = col_at(0);
@@ -93,13 +97,16 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
   const __amdgpu_buffer_rsrc_t vrsrc = make_rsrc(vbase, (slab_rows * a.v.sl + D) * 2);
   const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2), v_tile_bytes = (int32_t)(kTileK * a.v.sl * 2);
+  // (the second tile of a partial 128-key block may lie wholly past the end: any real tile is copied, all keys masked)
   auto copy_k = [&](int blk, char* dst) {
-    const int ub = __builtin_amdgcn_readfirstlane(blk);
+    const int rb = __builtin_amdgcn_readfirstlane(blk);
+    const int ub = rb < last_blk ? rb : last_blk;
     if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
     else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
   };
   auto copy_v = [&](int blk, char* dst) {
-    const int ub = __builtin_amdgcn_readfirstlane(blk);
+    const int rb = __builtin_amdgcn_readfirstlane(blk);
+    const int ub = rb < last_blk ? rb : last_blk;
     if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
     else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
   };
@@ -155,7 +162,8 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     copy_k(blk2, kb_free);                                                                         \
     copy_v(blk1, vb_free);                                                                         \
     const int blk_new = col_at((T) + 4);                                                           \
-    const int valid = (MASKED) ? ((__builtin_amdgcn_readfirstlane(blk0) == last_blk ? tail_keys : kTileK) - 32 * kh) : 32; \
+    const int tile0 = __builtin_amdgcn_readfirstlane(blk0);                                        \
+    const int valid = (MASKED) ? ((tile0 > last_blk ? 0 : tile0 == last_blk ? tail_keys : kTileK) - 32 * kh) : 32; \
     float alpha;                                                                                   \
     bool any_raise;                                                                                \
     logits_sub<D, 1, false>(kb_next, kh, kaddr, qf, S_NEXT);                                       \
@@ -188,8 +196,8 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
       SPARSED_SPLITK_STEP(1, false, t + 1, s_b, s_a);
       t += 2;
     }
-    if (n - t == 2) {
-      SPARSED_SPLITK_STEP(0, false, t, s_a, s_b);
+    if (n - t == 2) {  // the last two tiles may both be short (a partial 128-key block)
+      SPARSED_SPLITK_STEP(0, true, t, s_a, s_b);
       SPARSED_SPLITK_STEP(1, true, t + 1, s_b, s_a);
     } else {
       SPARSED_SPLITK_STEP(0, true, t, s_a, s_b);

@@ -103,13 +103,21 @@ void pool_bf16_kernel(const PoolArgs a) {
     asm volatile("" : "+v"(part));  // keep the vector work inside the block that holds the matrix work
     return part;
   };
-  auto flush_block = [&](int t, float part) {  // after the tile barrier: key block t is complete
+  const int tile_shift = a.block_k == 2 * kTileK ? 1 : 0;  // a 128-key block is pooled over two consecutive tiles
+  float block_acc = 0.f;                                   // thread 0: sum over the tiles of the block in progress
+  auto flush_block = [&](int t, float part) {  // after the tile barrier: key tile t is complete
     (void)part;
     if (tid == 0) {
-      float tot = 0.f;
+      float tot = block_acc;
 #pragma unroll
       for (int w = 0; w < NW; ++w) tot += wsum[t & 1][w];
-      arow[t] = tot * (1.0f / (float)(rows_here * keys_of(t)));  // mean over the entries that exist
+      if ((t & tile_shift) == tile_shift || t == n - 1) {  // last tile of its key block
+        const int J = t >> tile_shift;
+        const int keys_here = key_len - J * a.block_k < a.block_k ? key_len - J * a.block_k : a.block_k;
+        arow[J] = tot * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
+        tot = 0.f;
+      }
+      block_acc = tot;
     }
   };
 

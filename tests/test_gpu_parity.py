@@ -278,6 +278,11 @@ def test_dense_ragged_length(dtype, L, Hq, Hkv, D):
     (torch.bfloat16, 128, 64, 1000, 2, 2, 128, 0.25, False),
     (torch.bfloat16, 64, 64, 1100, 2, 1, 128, 0.2, True),
     (torch.bfloat16, 32, 64, 200, 2, 2, 64, 0.5, False),
+    (torch.bfloat16, 128, 128, 1000, 2, 2, 128, 0.3, False),   # the paper's square 128 blocks: last one 64 + 40 keys
+    (torch.bfloat16, 128, 128, 960, 2, 1, 128, 0.3, True),     # last block 64 keys: its second tile does not exist
+    (torch.bfloat16, 64, 128, 900, 2, 2, 128, 0.25, False),    # last block 4 keys
+    (torch.bfloat16, 32, 128, 1024, 2, 2, 64, 0.5, True),      # every block full
+    (torch.bfloat16, 128, 128, 100, 1, 1, 128, 1.0, False),    # a single partial block
     (torch.float32, 32, 32, 100, 2, 2, 64, 0.5, False),
     (torch.float32, 64, 64, 333, 1, 1, 64, 0.3, True),      # last 64-key block: 13 keys, its second 32-key tile is empty
     (torch.float32, 128, 32, 300, 2, 1, 128, 0.3, False),
@@ -322,6 +327,8 @@ def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_
     (torch.bfloat16, 64, 64, 1000, 128, 990, 0.25),    # inside the partial last block
     (torch.bfloat16, 32, 64, 512, 64, 1, 0.4),         # a single prefill key
     (torch.bfloat16, 128, 64, 1024, 128, 1023, 0.3),   # a single generation key
+    (torch.bfloat16, 128, 128, 1024, 128, 200, 0.3),   # 128-key blocks: boundary inside the second tile of block 1
+    (torch.bfloat16, 64, 128, 1000, 128, 930, 0.4),    # inside the partial last 128-key block
     (torch.float32, 32, 32, 256, 64, 50, 0.3),
     (torch.float32, 64, 64, 300, 64, 70, 0.4),         # 64-key blocks over 32-key tiles, partial last block
 ])
@@ -440,6 +447,7 @@ def test_calls_run_on_the_callers_stream():
 @pytest.mark.parametrize("dtype,bq,bk,L,D,lens,rho", [
     (torch.bfloat16, 128, 64, 1024, 128, [1024, 70, 333, 640], 0.25),
     (torch.bfloat16, 64, 64, 512, 64, [1, 512, 65, 129], 0.3),
+    (torch.bfloat16, 128, 128, 1024, 128, [1024, 70, 333, 640, 129], 0.3),   # 128-key blocks
     (torch.float32, 32, 32, 200, 64, [200, 33, 100], 0.4),
 ])
 def test_per_sample_lengths(dtype, bq, bk, L, D, lens, rho):
@@ -497,10 +505,39 @@ def _sweep_cases(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _sweep_cases(24, seed=2024), ids=lambda c: f"{c[0]}-{str(c[1])[6:]}-B{c[2]}H{c[3]}/{c[4]}-L{c[5]}-D{c[6]}-{c[7]}x{c[8]}-rho{c[9]}")
+def _sweep_cases_wide_key_blocks(n, seed):
+    """bf16 with 128-key blocks (the paper's square 128 x 128 among them): lengths chosen so that the last block is
+    often short, sometimes no longer than one 64-key tile."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        bq = int(rng.choice([32, 64, 128]))
+        Hkv = int(rng.choice([1, 2]))
+        Hq = Hkv * int(rng.choice([1, 2]))
+        B = int(rng.choice([1, 2]))
+        L = int(rng.integers(1, 1200))
+        rho = float(rng.choice([0.1, 0.3, 0.5, 1.0]))
+        cases.append((1000 + i, torch.bfloat16, B, Hq, Hkv, L, D, bq, 128, rho))
+    return cases
+
+
+_SWEEP_IDS = lambda c: f"{c[0]}-{str(c[1])[6:]}-B{c[2]}H{c[3]}/{c[4]}-L{c[5]}-D{c[6]}-{c[7]}x{c[8]}-rho{c[9]}"  # noqa: E731
+
+
+@pytest.mark.parametrize("case", _sweep_cases_wide_key_blocks(12, seed=77), ids=_SWEEP_IDS)
+def test_sweep_select_sparse_with_128_key_blocks(case):
+    _sweep_body(case)
+
+
+@pytest.mark.parametrize("case", _sweep_cases(24, seed=2024), ids=_SWEEP_IDS)
 def test_sweep_dense_select_sparse(case):
     """Every entry point on shapes drawn at random (seeded): any length from 1 up, both head dims, all block
     shapes, grouped heads, batch 1-2. Dense, selection (index inside the tie band) and sparse on the GPU's index."""
+    _sweep_body(case)
+
+
+def _sweep_body(case):
     i, dtype, B, Hq, Hkv, L, D, bq, bk, rho = case
     _say(f"sweep {case}")
     q, k, v = _rand_qkv(B, Hq, Hkv, L, D, dtype, seed=100 + i, scale=1.0 if dtype == torch.float32 and D == 64 else 0.5)
@@ -633,9 +670,10 @@ def test_window_index_matches_token_level_definition(L, bq, bk, window, sink):
     assert np.array_equal(ix.col_idx.cpu().numpy().reshape(H, -1)[:, :col.shape[1]], col)
 
 
-def test_window_index_feeds_the_sparse_kernel():
+@pytest.mark.parametrize("L,bq,bk", [(1024, 128, 64), (1000, 128, 128), (900, 64, 128)])
+def test_window_index_feeds_the_sparse_kernel(L, bq, bk):
     from oracle import patterns
-    L, bq, bk, H = 1024, 128, 64, 2
+    H = 2
     q, k, v = _rand_qkv(1, H, H, L, 128, torch.bfloat16, seed=77)
     ix = sd.index_fill_window(1, H, L, bq, bk, 256, 64, DEV)
     got = sd.attn_sparse(*_dev(q, k, v), ix)
