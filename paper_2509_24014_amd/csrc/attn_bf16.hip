@@ -22,7 +22,8 @@
 
 namespace sparsed {
 
-template <int D, int NQ, int NW, Mode MODE>
+// KB: keys per listed block in sparse mode (64 or 128), a compile-time choice.
+template <int D, int NQ, int NW, Mode MODE, int KB = kTileK>
 __global__ __launch_bounds__(NW * 64)
     __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? 2 : 1, (NQ == 1 && NW >= 4) ? 2 : 1))) void attn_bf16_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(NW * 64)
 
   // key tiles to visit
   // A listed key block of 128 keys is two consecutive 64-key tiles of the list.
-  const int tile_shift = (MODE == Mode::kSparse && a.block_k == 2 * kTileK) ? 1 : 0;
+  constexpr int tile_shift = (MODE == Mode::kSparse && KB == 2 * kTileK) ? 1 : 0;
   int n;
   const int32_t* cols = nullptr;
   if (MODE == Mode::kSparse) {
@@ -346,12 +347,12 @@ int dense_qtile_bf16(int L) {
   return L >= 1024 ? 256 : L >= 256 ? 128 : 64;  // partial last tile: waste at most one tile of rows
 }
 
-template <int D, int NQ, int NW, Mode MODE>
+template <int D, int NQ, int NW, Mode MODE, int KB = kTileK>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.n_qtiles;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)total), block(NW * 64);
-  hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE>), grid, block, 0, s, a);
+  hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, MODE, KB>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -359,7 +360,9 @@ template <int D, Mode MODE>
 static hipError_t launch_by_qtile(int qtile, const AttnArgs& a, hipStream_t s) {
   switch (qtile) {
     case 256: return launch_one<D, 1, 8, MODE>(a, s);
-    case 128: return launch_one<D, 1, 4, MODE>(a, s);
+    case 128:
+      if (MODE == Mode::kSparse && a.block_k == 2 * kTileK) return launch_one<D, 1, 4, MODE, 2 * kTileK>(a, s);
+      return launch_one<D, 1, 4, MODE>(a, s);
     case 64: return launch_one<D, 1, 2, MODE>(a, s);
     case 32: return launch_one<D, 1, 1, MODE>(a, s);
   }

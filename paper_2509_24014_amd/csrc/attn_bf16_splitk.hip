@@ -17,7 +17,8 @@
 
 namespace sparsed {
 
-template <int D, int RW>
+// KB: keys per listed block (32, 64 or 128), a compile-time choice so that the common 64 pays nothing for the others.
+template <int D, int RW, int KB>
 __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 2 ? 2 : 1, RW >= 2 ? 2 : 1))) void attn_bf16_splitk_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NW = 2 * RW, NT = NW * 64, QT = 32 * RW;
@@ -52,11 +53,17 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
 
   const int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1) + qt;
   const int beg = rp[0], end = rp[1];
-  const int tile_shift = a.block_k == 2 * kTileK ? 1 : 0;  // a listed 128-key block is two consecutive tiles
-  const int n = (end - beg) << tile_shift;
+  // A listed 128-key block is two consecutive tiles. Listed 32-key blocks are paired up in list order:
+  // tile t holds entries 2t and 2t + 1, one in each 32-key half, wherever in the sequence they come from
+  // (the key half a wave owns is then exactly one listed block; an odd count leaves the last half empty).
+  constexpr int tile_shift = KB == 2 * kTileK ? 1 : 0;
+  constexpr bool half_blocks = KB == kTileK / 2;
+  const int entries = end - beg;
+  const int n = half_blocks ? (entries + 1) >> 1 : entries << tile_shift;
   const int32_t* cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
-  const int last_blk = (L - 1) / kTileK;        // last key TILE that exists
-  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in it
+  constexpr int unit = half_blocks ? kTileK / 2 : kTileK;  // keys per copy unit: a 32-key block or a 64-key tile
+  const int last_blk = (L - 1) / unit;                 // last unit that exists
+  const int tail_keys = L - last_blk * unit;           // keys in it
 
   float M = -1e30f, lsum = 0.f;
   f32x16 o[1][D / 32];
@@ -69,8 +76,13 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
 
   TileDma<D, NT, false> kdma;
   TileDma<D, NT, true> vdma;
-  kdma.init(a.k.sl, wave, lane);
-  vdma.init(a.v.sl, wave, lane);
+  if (half_blocks) {
+    kdma.init_half(a.k.sl, wave, lane);
+    vdma.init_half(a.v.sl, wave, lane);
+  } else {
+    kdma.init(a.k.sl, wave, lane);
+    vdma.init(a.v.sl, wave, lane);
+  }
   KFragAddr<D> kaddr;
   VFragAddr<D> vaddr;
   kaddr.init(lane);
@@ -79,7 +91,11 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
   // block numbers of tiles t .. t+3, read with a vector load (see attn_bf16.hip); past the end: the last one
   int opaque_zero;
   asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
-  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list
+  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list; with 32-key blocks: the block of this wave's half
+    if (half_blocks) {
+      const int e = 2 * t + kh;
+      return cols[(e < entries ? e : (entries > 0 ? entries - 1 : 0)) + opaque_zero];  // a missing half repeats the last block, masked
+    }
     const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
     return (cols[(idx >> tile_shift) + opaque_zero] << tile_shift) + (idx & tile_shift);
   };
@@ -96,19 +112,27 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
   const int64_t slab_rows = (int64_t)(a.L - 1);
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
   const __amdgpu_buffer_rsrc_t vrsrc = make_rsrc(vbase, (slab_rows * a.v.sl + D) * 2);
-  const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2), v_tile_bytes = (int32_t)(kTileK * a.v.sl * 2);
+  const int32_t k_tile_bytes = (int32_t)(unit * a.k.sl * 2), v_tile_bytes = (int32_t)(unit * a.v.sl * 2);  // bytes per copy unit
   // (the second tile of a partial 128-key block may lie wholly past the end: any real tile is copied, all keys masked)
   auto copy_k = [&](int blk, char* dst) {
     const int rb = __builtin_amdgcn_readfirstlane(blk);
     const int ub = rb < last_blk ? rb : last_blk;
-    if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
-    else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
+    if (ub == last_blk && tail_keys < unit) {
+      if (half_blocks) kdma.issue_partial_half(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
+      else kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, lane, a.k.sl, tail_keys);
+    } else {
+      kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
+    }
   };
   auto copy_v = [&](int blk, char* dst) {
     const int rb = __builtin_amdgcn_readfirstlane(blk);
     const int ub = rb < last_blk ? rb : last_blk;
-    if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
-    else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
+    if (ub == last_blk && tail_keys < unit) {
+      if (half_blocks) vdma.issue_partial_half(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
+      else vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, lane, a.v.sl, tail_keys);
+    } else {
+      vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
+    }
   };
 
   const float c = a.scale_log2;
@@ -163,7 +187,9 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     copy_v(blk1, vb_free);                                                                         \
     const int blk_new = col_at((T) + 4);                                                           \
     const int tile0 = __builtin_amdgcn_readfirstlane(blk0);                                        \
-    const int valid = (MASKED) ? ((tile0 > last_blk ? 0 : tile0 == last_blk ? tail_keys : kTileK) - 32 * kh) : 32; \
+    const int valid = !(MASKED) ? 32                                                               \
+                      : half_blocks ? (2 * (T) + kh < entries ? (tile0 == last_blk ? tail_keys : 32) : 0) \
+                                    : (tile0 > last_blk ? 0 : tile0 == last_blk ? tail_keys : kTileK) - 32 * kh; \
     float alpha;                                                                                   \
     bool any_raise;                                                                                \
     logits_sub<D, 1, false>(kb_next, kh, kaddr, qf, S_NEXT);                                       \
@@ -196,8 +222,8 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
       SPARSED_SPLITK_STEP(1, false, t + 1, s_b, s_a);
       t += 2;
     }
-    if (n - t == 2) {  // the last two tiles may both be short (a partial 128-key block)
-      SPARSED_SPLITK_STEP(0, true, t, s_a, s_b);
+    if (n - t == 2) {  // with 128-key blocks the last two tiles may both be short (a partial last block)
+      SPARSED_SPLITK_STEP(0, (tile_shift != 0), t, s_a, s_b);
       SPARSED_SPLITK_STEP(1, true, t + 1, s_b, s_a);
     } else {
       SPARSED_SPLITK_STEP(0, true, t, s_a, s_b);
@@ -264,7 +290,13 @@ template <int D, int RW>
 static hipError_t launch_splitk(const AttnArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.n_qtiles;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((attn_bf16_splitk_kernel<D, RW>), dim3((unsigned)total), dim3(RW * 128), 0, s, a);
+  const dim3 grid((unsigned)total), block(RW * 128);
+  switch (a.block_k) {
+    case 32: hipLaunchKernelGGL((attn_bf16_splitk_kernel<D, RW, 32>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((attn_bf16_splitk_kernel<D, RW, 64>), grid, block, 0, s, a); break;
+    case 128: hipLaunchKernelGGL((attn_bf16_splitk_kernel<D, RW, 128>), grid, block, 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

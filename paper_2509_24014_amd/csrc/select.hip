@@ -30,7 +30,8 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float x) {
 // the attention kernels: sub-step u interleaves the matrix work S(u+1) = K(u+1) Q^T with the vector
 // work of sub-tile u (p = 2^(s*c - lse), summed per lane). A key block is two sub-tiles; its
 // per-lane sums are reduced over the wave, then over the waves through LDS in a fixed order.
-template <int D, int NW>
+// HALF: key blocks of 32 (the two 32-key sub-tiles of a tile are pooled separately).
+template <int D, int NW, bool HALF>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2 ? 2 : 1, NW >= 2 ? 2 : 1)))
 void pool_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
@@ -39,6 +40,7 @@ void pool_bf16_kernel(const PoolArgs a) {
   __shared__ __attribute__((aligned(1024))) char kbuf0[kKBytes];
   __shared__ __attribute__((aligned(1024))) char kbuf1[kKBytes];
   __shared__ float wsum[2][NW];
+  __shared__ float wsum_even[2][NW];  // HALF only: the even sub-tile's sums (wsum then holds the odd one's)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -108,6 +110,18 @@ void pool_bf16_kernel(const PoolArgs a) {
   auto flush_block = [&](int t, float part) {  // after the tile barrier: key tile t is complete
     (void)part;
     if (tid == 0) {
+      if (HALF) {  // two 32-key blocks per tile; the second may not exist in the last tile
+        float ev = 0.f, od = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          ev += wsum_even[t & 1][w];
+          od += wsum[t & 1][w];
+        }
+        const int left = key_len - t * kTileK;  // keys from this tile's first on
+        arow[2 * t] = ev * (1.0f / (float)(rows_here * (left < 32 ? left : 32)));
+        if (left > 32) arow[2 * t + 1] = od * (1.0f / (float)(rows_here * (left - 32 < 32 ? left - 32 : 32)));
+        return;
+      }
       float tot = block_acc;
 #pragma unroll
       for (int w = 0; w < NW; ++w) tot += wsum[t & 1][w];
@@ -132,10 +146,14 @@ void pool_bf16_kernel(const PoolArgs a) {
     if (MASKED) copy_k_any((T) + 2, kb_free);                                                      \
     else kdma.issue(krsrc, ((T) + 2 < n ? (T) + 2 : n - 1) * k_tile_bytes, kb_free, wave);         \
     logits_sub<D, 1, false>(kb_next, 0, kaddr, qf, s_even);                                        \
-    float part = carry + expsum_sub(s_odd, (MASKED), keys_at(T) - 32);                             \
+    float part = (HALF ? 0.f : carry) + expsum_sub(s_odd, (MASKED), keys_at(T) - 32);              \
     sched_substep_interleave<D, 1, false>();                                                       \
     part = wave_sum_to_last_lane(part);                                                            \
     if (lane == 63) wsum[(P)][wave] = part;                                                        \
+    if (HALF) {                                                                                    \
+      const float ev = wave_sum_to_last_lane(carry);                                               \
+      if (lane == 63) wsum_even[(P)][wave] = ev;                                                   \
+    }                                                                                              \
     __builtin_amdgcn_sched_barrier(0);                                                             \
     logits_sub<D, 1, false>(kb_next, 1, kaddr, qf, s_odd);                                         \
     carry = expsum_sub(s_even, (MASKED), keys_at((T) + 1));                                        \
@@ -427,11 +445,18 @@ template <int D>
 static hipError_t launch_pool_bf16_d(int block_q, const PoolArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.nqb;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
+  if (a.block_k == 32 && block_q > 64) return hipErrorInvalidValue;  // 32-key blocks go with query blocks of 32 or 64 rows
   const dim3 grid((unsigned)total);
   switch (block_q) {
-    case 128: hipLaunchKernelGGL((pool_bf16_kernel<D, 4>), grid, dim3(256), 0, s, a); break;
-    case 64: hipLaunchKernelGGL((pool_bf16_kernel<D, 2>), grid, dim3(128), 0, s, a); break;
-    case 32: hipLaunchKernelGGL((pool_bf16_kernel<D, 1>), grid, dim3(64), 0, s, a); break;
+    case 128: hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false>), grid, dim3(256), 0, s, a); break;
+    case 64:
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 2, true>), grid, dim3(128), 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 2, false>), grid, dim3(128), 0, s, a);
+      break;
+    case 32:
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 1, true>), grid, dim3(64), 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 1, false>), grid, dim3(64), 0, s, a);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -159,6 +159,34 @@ struct TileDma {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, row * row_bytes + chunk * 16, tile_byte_offset, 0, 0);
     }
   }
+  // 32-key blocks: a tile is put together from two independent 32-row halves. With at least two waves
+  // every wave's loads lie in ONE half; init_half makes its offsets relative to that half's first row,
+  // and issue() is then given the byte offset of the 32-key block that belongs in this wave's half.
+  static constexpr bool kWaveInOneHalf = 2 * kPerWave <= kWaveLoads;
+  __device__ __forceinline__ void init_half(int64_t stride_l, int wave_in_group, int lane) {
+    static_assert(kWaveInOneHalf, "needs at least two waves");
+    init(stride_l, wave_in_group, lane);
+    if (2 * wave_in_group * kPerWave >= kWaveLoads) {
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) goff[u] -= (int32_t)(32 * stride_l * 2);
+    }
+  }
+  // the same for a 32-key block of which only the first `rows` rows exist (the last block of a sequence)
+  __device__ __forceinline__ void issue_partial_half(__amdgpu_buffer_rsrc_t rsrc, int32_t block_byte_offset, char* lds_tile,
+                                                     int wave_in_group, int lane, int64_t stride_l, int rows) const {
+    asm volatile("" : "+v"(lane));  // worked out afresh at every call, as in issue_partial
+    const int32_t row_bytes = (int32_t)(stride_l * 2);
+#pragma unroll
+    for (int u = 0; u < kPerWave; ++u) {
+      const int wl = wave_in_group * kPerWave + u;
+      int row, chunk;
+      source_of(wl, lane, &row, &chunk);
+      row &= 31;  // row within the half
+      if (row >= rows) row = rows - 1;
+      char* dst = lds_tile + lds_piece_offset(wl);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, row * row_bytes + chunk * 16, block_byte_offset, 0, 0);
+    }
+  }
   // rsrc: buffer descriptor of the (batch, head) slab; tile_byte_offset: wave-uniform byte offset of
   // the tile's first row in it; lds_tile: LDS address of the tile. The buffer form of the direct
   // load is used because the compiler accounts for it on the vector-memory counter only; the

@@ -283,6 +283,11 @@ def test_dense_ragged_length(dtype, L, Hq, Hkv, D):
     (torch.bfloat16, 64, 128, 900, 2, 2, 128, 0.25, False),    # last block 4 keys
     (torch.bfloat16, 32, 128, 1024, 2, 2, 64, 0.5, True),      # every block full
     (torch.bfloat16, 128, 128, 100, 1, 1, 128, 1.0, False),    # a single partial block
+    (torch.bfloat16, 32, 32, 1000, 2, 2, 128, 0.5, False),     # the paper's square 32 blocks: last one 8 keys
+    (torch.bfloat16, 32, 32, 992, 2, 1, 64, 0.5, True),        # 31 full blocks: the last tile has one block only
+    (torch.bfloat16, 64, 32, 1024, 2, 2, 128, 0.3, False),
+    (torch.bfloat16, 64, 32, 50, 1, 1, 128, 1.0, False),       # one tile: a full block and a partial one
+    (torch.bfloat16, 32, 32, 20, 1, 1, 64, 1.0, True),         # a single partial block
     (torch.float32, 32, 32, 100, 2, 2, 64, 0.5, False),
     (torch.float32, 64, 64, 333, 1, 1, 64, 0.3, True),      # last 64-key block: 13 keys, its second 32-key tile is empty
     (torch.float32, 128, 32, 300, 2, 1, 128, 0.3, False),
@@ -329,6 +334,8 @@ def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_
     (torch.bfloat16, 128, 64, 1024, 128, 1023, 0.3),   # a single generation key
     (torch.bfloat16, 128, 128, 1024, 128, 200, 0.3),   # 128-key blocks: boundary inside the second tile of block 1
     (torch.bfloat16, 64, 128, 1000, 128, 930, 0.4),    # inside the partial last 128-key block
+    (torch.bfloat16, 32, 32, 512, 128, 77, 0.5),       # 32-key blocks
+    (torch.bfloat16, 64, 32, 500, 64, 490, 0.4),       # inside the partial last 32-key block
     (torch.float32, 32, 32, 256, 64, 50, 0.3),
     (torch.float32, 64, 64, 300, 64, 70, 0.4),         # 64-key blocks over 32-key tiles, partial last block
 ])
@@ -448,6 +455,7 @@ def test_calls_run_on_the_callers_stream():
     (torch.bfloat16, 128, 64, 1024, 128, [1024, 70, 333, 640], 0.25),
     (torch.bfloat16, 64, 64, 512, 64, [1, 512, 65, 129], 0.3),
     (torch.bfloat16, 128, 128, 1024, 128, [1024, 70, 333, 640, 129], 0.3),   # 128-key blocks
+    (torch.bfloat16, 32, 32, 512, 64, [512, 33, 100, 1, 480], 0.5),          # 32-key blocks
     (torch.float32, 32, 32, 200, 64, [200, 33, 100], 0.4),
 ])
 def test_per_sample_lengths(dtype, bq, bk, L, D, lens, rho):
@@ -527,6 +535,27 @@ _SWEEP_IDS = lambda c: f"{c[0]}-{str(c[1])[6:]}-B{c[2]}H{c[3]}/{c[4]}-L{c[5]}-D{
 
 @pytest.mark.parametrize("case", _sweep_cases_wide_key_blocks(12, seed=77), ids=_SWEEP_IDS)
 def test_sweep_select_sparse_with_128_key_blocks(case):
+    _sweep_body(case)
+
+
+def _sweep_cases_narrow_key_blocks(n, seed):
+    """bf16 with 32-key blocks (the paper's square 32 x 32 among them): listed blocks are paired up two to a tile."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        bq = int(rng.choice([32, 64]))
+        Hkv = int(rng.choice([1, 2]))
+        Hq = Hkv * int(rng.choice([1, 2]))
+        B = int(rng.choice([1, 2]))
+        L = int(rng.integers(1, 700))
+        rho = float(rng.choice([0.1, 0.3, 0.5, 1.0]))
+        cases.append((2000 + i, torch.bfloat16, B, Hq, Hkv, L, D, bq, 32, rho))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases_narrow_key_blocks(12, seed=78), ids=_SWEEP_IDS)
+def test_sweep_select_sparse_with_32_key_blocks(case):
     _sweep_body(case)
 
 
@@ -670,7 +699,7 @@ def test_window_index_matches_token_level_definition(L, bq, bk, window, sink):
     assert np.array_equal(ix.col_idx.cpu().numpy().reshape(H, -1)[:, :col.shape[1]], col)
 
 
-@pytest.mark.parametrize("L,bq,bk", [(1024, 128, 64), (1000, 128, 128), (900, 64, 128)])
+@pytest.mark.parametrize("L,bq,bk", [(1024, 128, 64), (1000, 128, 128), (900, 64, 128), (1000, 32, 32), (700, 64, 32)])
 def test_window_index_feeds_the_sparse_kernel(L, bq, bk):
     from oracle import patterns
     H = 2
