@@ -891,6 +891,10 @@ def test_workload_long64k_sampled():
     _check_workload_sampled("long64k", n_per_type=3)
 
 
+def test_papers_own_long_context_setting_sampled():
+    _check_workload_sampled("paper64k", n_per_type=2)
+
+
 def test_twice_the_papers_longest_context_sampled():
     _check_workload_sampled("probe128k", n_per_type=2)
 

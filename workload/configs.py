@@ -49,6 +49,9 @@ CONFIGS = {
     # Not one of the five named workloads: a short-running shape (same head dim, blocks and generator as
     # the long-context one) for hardware-counter runs, whose 32-bit counters saturate on longer kernels.
     "probe8k": WorkloadConfig("probe8k", 6, 1, 8, 8, 8192, 128, "bf16", 128, 64, 0.1, 1, 1, 0.0, True),
+    # The paper's own long-context setting (Section 4.1: square blocks of 128, rho = 30 %, skip = 20 %) on the
+    # long-context shape: not one of the five named workloads, used for one parity test and one line of measurements.
+    "paper64k": WorkloadConfig("paper64k", 8, 1, 32, 32, 65536, 128, "bf16", 128, 128, 0.3, 1024, 205, 0.02, True),
     # Not one of the five named workloads either: twice the longest context the paper runs, four heads (one of
     # each planted type), used by one parity test to show that nothing in the path stops at 64k.
     "probe128k": WorkloadConfig("probe128k", 7, 1, 4, 4, 131072, 128, "bf16", 128, 64, 0.05, 1, 1, 0.0, True),
