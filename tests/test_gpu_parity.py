@@ -291,6 +291,8 @@ def test_dense_ragged_length(dtype, L, Hq, Hkv, D):
     (torch.float32, 32, 32, 100, 2, 2, 64, 0.5, False),
     (torch.float32, 64, 64, 333, 1, 1, 64, 0.3, True),      # last 64-key block: 13 keys, its second 32-key tile is empty
     (torch.float32, 128, 32, 300, 2, 1, 128, 0.3, False),
+    (torch.float32, 128, 128, 300, 2, 1, 128, 0.4, False),     # fp32, 128-key blocks over 32-key tiles: last block 44 keys
+    (torch.float32, 32, 128, 520, 2, 2, 64, 0.3, True),        # last block 8 keys
 ])
 def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_lse):
     _say(f"select+sparse ragged {dtype} {bq}x{bk} L={L}")
@@ -338,6 +340,7 @@ def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_
     (torch.bfloat16, 64, 32, 500, 64, 490, 0.4),       # inside the partial last 32-key block
     (torch.float32, 32, 32, 256, 64, 50, 0.3),
     (torch.float32, 64, 64, 300, 64, 70, 0.4),         # 64-key blocks over 32-key tiles, partial last block
+    (torch.float32, 128, 128, 400, 128, 150, 0.4),     # fp32, 128-key blocks
 ])
 def test_isolated_selection_with_the_boundary_inside_a_block(dtype, bq, bk, L, D, ptok, rho):
     _say(f"isolated selection, token boundary: {dtype} {bq}x{bk} L={L} p={ptok}")
