@@ -29,8 +29,8 @@
  *  - Grouped-query attention: q has Hq heads, k and v have Hkv heads with
  *    Hq % Hkv == 0; query head h reads key/value head h / (Hq / Hkv).
  *  - Supported shapes: D in {64, 128}; any L >= 1; block_q in {32, 64, 128};
- *    block_k in {32, 64, 128} (bf16: 32 only with block_q 32 or 64); the paper's
- *    square settings 32 x 32 and 128 x 128 are among them. L need not be a
+ *    block_k in {32, 64, 128}; the paper's square settings 32 x 32 and 128 x 128
+ *    are among them. L need not be a
  *    multiple of the block sizes: there are nqb = ceil(L / block_q) query blocks
  *    and nkb = ceil(L / block_k) key blocks, the last of each possibly partial
  *    (the paper pools with L // block_size and is silent on a remainder).

@@ -71,7 +71,6 @@ sparsed_status check_out(const sparsed_tensor* q, const sparsed_tensor* out) {
 sparsed_status check_blocks(const sparsed_tensor* q, int bq, int bk) {
   if (bq != 32 && bq != 64 && bq != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_q %d not in {32,64,128}", bq);
   if (q->dtype == SPARSED_BF16 && bk != 32 && bk != 64 && bk != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64,128} (bf16)", bk);
-  if (q->dtype == SPARSED_BF16 && bk == 32 && bq > 64) return fail(SPARSED_ERR_UNSUPPORTED, "bf16 block_k 32 goes with block_q 32 or 64, not %d", bq);
   if (q->dtype == SPARSED_F32 && bk != 32 && bk != 64 && bk != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64,128}", bk);
   return SPARSED_OK;
 }

@@ -63,23 +63,31 @@ __global__ __launch_bounds__(NW * 64)
   const int row0 = qt * QT + wave * (32 * NQ);  // first query row of this wave
 
   // key tiles to visit
-  // A listed key block of 128 keys is two consecutive 64-key tiles of the list.
+  // A listed key block of 128 keys is two consecutive 64-key tiles of the list. Listed 32-key blocks are
+  // paired up in list order: tile t holds entries 2t and 2t + 1, one in each 32-key half, wherever in
+  // the sequence they come from (an odd count leaves the last half empty); the waves that copy the
+  // upper half of a tile track entry 2t + 1, the others entry 2t.
   constexpr int tile_shift = (MODE == Mode::kSparse && KB == 2 * kTileK) ? 1 : 0;
-  int n;
+  constexpr bool half_blocks = MODE == Mode::kSparse && KB == kTileK / 2;
+  constexpr int unit = half_blocks ? kTileK / 2 : kTileK;  // keys per copy unit: a 32-key block or a 64-key tile
+  static_assert(!half_blocks || NW >= 2, "32-key blocks need a wave per tile half");
+  const int my_half = (half_blocks && 2 * wave >= NW) ? 1 : 0;
+  int n, entries = 0;
   const int32_t* cols = nullptr;
   if (MODE == Mode::kSparse) {
     const int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1) + qt;
     const int beg = rp[0], end = rp[1];
-    n = (end - beg) << tile_shift;
+    entries = end - beg;
+    n = half_blocks ? (entries + 1) >> 1 : entries << tile_shift;
     cols = a.col_idx + (int64_t)bh * a.cap_per_head + beg;
   } else {
     n = (L + kTileK - 1) / kTileK;
   }
-  // A sequence length that is not a multiple of the tile leaves the last key tile partial: its
-  // missing keys are masked to -inf in the softmax and its missing rows never fetched. The second tile
-  // of a partial 128-key block may lie wholly past the end: no keys, every logit masked.
-  const int last_blk = (L - 1) / kTileK;        // last key TILE that exists
-  const int tail_keys = L - last_blk * kTileK;  // 1 .. 64 keys in it
+  // A sequence length that is not a multiple of the unit leaves the last one partial: its missing keys
+  // are masked to -inf in the softmax and its missing rows never fetched. The second tile of a partial
+  // 128-key block may lie wholly past the end: no keys, every logit masked.
+  const int last_blk = (L - 1) / unit;        // last key tile (32-key blocks: last block) that exists
+  const int tail_keys = L - last_blk * unit;  // keys in it
   auto keys_of = [&](int blk) -> int { return blk > last_blk ? 0 : blk == last_blk ? tail_keys : kTileK; };
 
   float M[NQ], lsum[NQ];
@@ -98,8 +106,13 @@ __global__ __launch_bounds__(NW * 64)
 
   TileDma<D, NT, false> kdma;
   TileDma<D, NT, true> vdma;
-  kdma.init(a.k.sl, wave, lane);
-  if (kHasV) vdma.init(a.v.sl, wave, lane);
+  if constexpr (half_blocks) {
+    kdma.init_half(a.k.sl, wave, lane);
+    vdma.init_half(a.v.sl, wave, lane);
+  } else {
+    kdma.init(a.k.sl, wave, lane);
+    if (kHasV) vdma.init(a.v.sl, wave, lane);
+  }
   KFragAddr<D> kaddr;
   VFragAddr<D> vaddr;
   kaddr.init(lane);
@@ -113,7 +126,11 @@ __global__ __launch_bounds__(NW * 64)
   asm volatile("v_mov_b32 %0, 0" : "=v"(opaque_zero));
   // Tiles past the end of the list repeat the last one: the steady loop prefetches up to two tiles
   // ahead without asking whether they exist, and a repeated copy of a real tile into a free buffer is harmless.
-  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list
+  auto col_at = [&](int t) -> int {  // key TILE number of tile t of the list; 32-key blocks: the block in this wave's copy half
+    if (half_blocks) {
+      const int e = 2 * t + my_half;
+      return cols[(e < entries ? e : (entries > 0 ? entries - 1 : 0)) + opaque_zero];  // a missing half repeats the last block, masked
+    }
     const int idx = t < n ? t : (n > 0 ? n - 1 : 0);
     if (MODE != Mode::kSparse) return idx;
     return (cols[(idx >> tile_shift) + opaque_zero] << tile_shift) + (idx & tile_shift);
@@ -132,10 +149,15 @@ __global__ __launch_bounds__(NW * 64)
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
   // keys that exist in tile number `tile` of the list (block `blk`): none past the end of the list
   auto keys_at = [&](int tile, int blk) -> int { return tile < n ? keys_of(uni(blk)) : 0; };
+  // 32-key blocks: keys that exist in list entry e (= half e % 2 of tile e / 2). Rows ascend, so only the
+  // last entry can be the partial last block of the sequence.
+  bool last_is_tail = false;
+  if (half_blocks && entries > 0) last_is_tail = __builtin_amdgcn_readfirstlane(cols[entries - 1 + opaque_zero]) == last_blk;
+  auto half_keys = [&](int e) -> int { return e < entries ? ((e == entries - 1 && last_is_tail) ? tail_keys : kTileK / 2) : 0; };
   const int64_t slab_rows = (int64_t)(a.L - 1);
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
   const __amdgpu_buffer_rsrc_t vrsrc = make_rsrc(kHasV ? vbase : kbase, kHasV ? (slab_rows * a.v.sl + D) * 2 : 0);
-  const int32_t k_tile_bytes = (int32_t)(kTileK * a.k.sl * 2), v_tile_bytes = (int32_t)(kTileK * a.v.sl * 2);
+  const int32_t k_tile_bytes = (int32_t)(unit * a.k.sl * 2), v_tile_bytes = (int32_t)(unit * a.v.sl * 2);  // per copy unit
   auto copy_k = [&](int blk, char* dst) { kdma.issue(krsrc, uni(blk) * k_tile_bytes, dst, wave); };
   auto copy_v = [&](int blk, char* dst) { vdma.issue(vrsrc, uni(blk) * v_tile_bytes, dst, wave); };
   // the same for a tile that may be the partial last block (prologue and the last few tiles only)
@@ -143,13 +165,21 @@ __global__ __launch_bounds__(NW * 64)
   // per-lane addresses of a partial copy are worked out there and not carried across the steady loop.)
   auto copy_k_any = [&](int blk, char* dst, int ln) {
     const int ub = uni(blk) < last_blk ? uni(blk) : last_blk;  // a tile past the end: any real tile will do
-    if (ub == last_blk && tail_keys < kTileK) kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, ln, a.k.sl, tail_keys);
-    else kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
+    if (ub == last_blk && tail_keys < unit) {
+      if constexpr (half_blocks) kdma.issue_partial_half(krsrc, ub * k_tile_bytes, dst, wave, ln, a.k.sl, tail_keys);
+      else kdma.issue_partial(krsrc, ub * k_tile_bytes, dst, wave, ln, a.k.sl, tail_keys);
+    } else {
+      kdma.issue(krsrc, ub * k_tile_bytes, dst, wave);
+    }
   };
   auto copy_v_any = [&](int blk, char* dst, int ln) {
     const int ub = uni(blk) < last_blk ? uni(blk) : last_blk;
-    if (ub == last_blk && tail_keys < kTileK) vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, ln, a.v.sl, tail_keys);
-    else vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
+    if (ub == last_blk && tail_keys < unit) {
+      if constexpr (half_blocks) vdma.issue_partial_half(vrsrc, ub * v_tile_bytes, dst, wave, ln, a.v.sl, tail_keys);
+      else vdma.issue_partial(vrsrc, ub * v_tile_bytes, dst, wave, ln, a.v.sl, tail_keys);
+    } else {
+      vdma.issue(vrsrc, ub * v_tile_bytes, dst, wave);
+    }
   };
   int lane_tail = lane;
 
@@ -239,8 +269,8 @@ __global__ __launch_bounds__(NW * 64)
       copy_k(blk2, kb_free);                                                                       \
       if (kHasV) copy_v(blk1, vb_free);                                                            \
     }                                                                                              \
-    const int valid_odd = (MASKED) ? keys_at((T), blk0) - 32 : 32;                                 \
-    const int valid_even = (MASKED) ? keys_at((T) + 1, blk1) : 32;                                 \
+    const int valid_odd = !(MASKED) ? 32 : half_blocks ? half_keys(2 * (T) + 1) : keys_at((T), blk0) - 32;     \
+    const int valid_even = !(MASKED) ? 32 : half_blocks ? half_keys(2 * (T) + 2) : keys_at((T) + 1, blk1);     \
     const int blk_new = col_at((T) + 4);                                                           \
     float alpha[NQ];                                                                               \
     bool any_raise;                                                                                \
@@ -273,14 +303,15 @@ __global__ __launch_bounds__(NW * 64)
     {
       float alpha[NQ];
       bool any_raise;
-      softmax_sub(s_even, p_even, alpha, any_raise, true, keys_at(0, blk0));  // O is still zero: nothing to rescale
+      softmax_sub(s_even, p_even, alpha, any_raise, true, half_blocks ? half_keys(0) : keys_at(0, blk0));  // O is still zero: nothing to rescale
     }
     __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
     // An unmasked step at tile t touches tiles t, t+1 (softmax) and t+2 (copy, possibly a repeat). A partial
     // last block must stay out of its reach on all three counts; a full last block only as far as t+1.
     // (with 128-key blocks the last block's second tile may not exist at all: same treatment)
-    const int steady_reach = (tail_keys < kTileK || (tile_shift && !(last_blk & 1))) ? 4 : 2;
+    // (and with 32-key blocks an odd count leaves the last tile's second half empty)
+    const int steady_reach = (tail_keys < unit || (tile_shift && !(last_blk & 1)) || (half_blocks && (entries & 1))) ? 4 : 2;
     int t = 0;
     while (t + steady_reach < n) {
       SPARSED_TILE_STEP(0, false, t);
@@ -362,6 +393,7 @@ static hipError_t launch_by_qtile(int qtile, const AttnArgs& a, hipStream_t s) {
     case 256: return launch_one<D, 1, 8, MODE>(a, s);
     case 128:
       if (MODE == Mode::kSparse && a.block_k == 2 * kTileK) return launch_one<D, 1, 4, MODE, 2 * kTileK>(a, s);
+      if (MODE == Mode::kSparse && a.block_k == kTileK / 2) return launch_one<D, 1, 4, MODE, kTileK / 2>(a, s);
       return launch_one<D, 1, 4, MODE>(a, s);
     case 64: return launch_one<D, 1, 2, MODE>(a, s);
     case 32: return launch_one<D, 1, 1, MODE>(a, s);

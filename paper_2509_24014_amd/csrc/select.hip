@@ -445,10 +445,12 @@ template <int D>
 static hipError_t launch_pool_bf16_d(int block_q, const PoolArgs& a, hipStream_t s) {
   const int64_t total = (int64_t)a.B * a.Hq * a.nqb;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
-  if (a.block_k == 32 && block_q > 64) return hipErrorInvalidValue;  // 32-key blocks go with query blocks of 32 or 64 rows
   const dim3 grid((unsigned)total);
   switch (block_q) {
-    case 128: hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false>), grid, dim3(256), 0, s, a); break;
+    case 128:
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 4, true>), grid, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false>), grid, dim3(256), 0, s, a);
+      break;
     case 64:
       if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 2, true>), grid, dim3(128), 0, s, a);
       else hipLaunchKernelGGL((pool_bf16_kernel<D, 2, false>), grid, dim3(128), 0, s, a);

@@ -82,7 +82,6 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(_ix(nkb=4)), None) == 8   # index vs q
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, None, None) == 1
     qb = _t(dtype=binding.SPARSED_BF16, D=128)
-    assert lib.sparsed_select_pattern(R(qb), R(qb), 128, 32, 0.3, R(_ix(nqb=2, nkb=8, bq=128, bk=32)), None) == 6  # bf16: 32-key blocks need bq <= 64
     assert lib.sparsed_select_pattern(R(qb), R(qb), 64, 16, 0.3, R(_ix(nqb=4, nkb=16, bq=64, bk=16)), None) == 6   # bf16 bk
     ex = binding._Exec(None, 0x4000, 16, None, None, None)
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(ix), R(ex)) == 7          # workspace too small

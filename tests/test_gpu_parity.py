@@ -288,6 +288,9 @@ def test_dense_ragged_length(dtype, L, Hq, Hkv, D):
     (torch.bfloat16, 64, 32, 1024, 2, 2, 128, 0.3, False),
     (torch.bfloat16, 64, 32, 50, 1, 1, 128, 1.0, False),       # one tile: a full block and a partial one
     (torch.bfloat16, 32, 32, 20, 1, 1, 64, 1.0, True),         # a single partial block
+    (torch.bfloat16, 128, 32, 1000, 2, 2, 128, 0.3, False),    # 128-row query blocks over 32-key blocks: last block 8 keys
+    (torch.bfloat16, 128, 32, 992, 2, 1, 64, 0.5, True),       # odd number of blocks
+    (torch.bfloat16, 128, 32, 40, 1, 1, 128, 1.0, False),      # one tile: a full block and a partial one
     (torch.float32, 32, 32, 100, 2, 2, 64, 0.5, False),
     (torch.float32, 64, 64, 333, 1, 1, 64, 0.3, True),      # last 64-key block: 13 keys, its second 32-key tile is empty
     (torch.float32, 128, 32, 300, 2, 1, 128, 0.3, False),
@@ -338,6 +341,7 @@ def test_select_and_sparse_ragged_length(dtype, bq, bk, L, Hq, Hkv, D, rho, use_
     (torch.bfloat16, 64, 128, 1000, 128, 930, 0.4),    # inside the partial last 128-key block
     (torch.bfloat16, 32, 32, 512, 128, 77, 0.5),       # 32-key blocks
     (torch.bfloat16, 64, 32, 500, 64, 490, 0.4),       # inside the partial last 32-key block
+    (torch.bfloat16, 128, 32, 640, 128, 333, 0.3),     # 128-row query blocks over 32-key blocks
     (torch.float32, 32, 32, 256, 64, 50, 0.3),
     (torch.float32, 64, 64, 300, 64, 70, 0.4),         # 64-key blocks over 32-key tiles, partial last block
     (torch.float32, 128, 128, 400, 128, 150, 0.4),     # fp32, 128-key blocks
@@ -547,7 +551,7 @@ def _sweep_cases_narrow_key_blocks(n, seed):
     cases = []
     for i in range(n):
         D = int(rng.choice([64, 128]))
-        bq = int(rng.choice([32, 64]))
+        bq = int(rng.choice([32, 64, 128]))
         Hkv = int(rng.choice([1, 2]))
         Hq = Hkv * int(rng.choice([1, 2]))
         B = int(rng.choice([1, 2]))
@@ -557,7 +561,7 @@ def _sweep_cases_narrow_key_blocks(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _sweep_cases_narrow_key_blocks(12, seed=78), ids=_SWEEP_IDS)
+@pytest.mark.parametrize("case", _sweep_cases_narrow_key_blocks(16, seed=78), ids=_SWEEP_IDS)
 def test_sweep_select_sparse_with_32_key_blocks(case):
     _sweep_body(case)
 
@@ -702,7 +706,7 @@ def test_window_index_matches_token_level_definition(L, bq, bk, window, sink):
     assert np.array_equal(ix.col_idx.cpu().numpy().reshape(H, -1)[:, :col.shape[1]], col)
 
 
-@pytest.mark.parametrize("L,bq,bk", [(1024, 128, 64), (1000, 128, 128), (900, 64, 128), (1000, 32, 32), (700, 64, 32)])
+@pytest.mark.parametrize("L,bq,bk", [(1024, 128, 64), (1000, 128, 128), (900, 64, 128), (1000, 32, 32), (700, 64, 32), (1000, 128, 32)])
 def test_window_index_feeds_the_sparse_kernel(L, bq, bk):
     from oracle import patterns
     H = 2
