@@ -11,7 +11,9 @@
 // Per tile step t a wave computes  S(t+1) = K(t+1)[half] Q^T  interleaved with the softmax of S(t),
 // then  O += P(t) V(t)[half].  K(t+2) and V(t+1) are copied global -> LDS meanwhile; one barrier per tile.
 // Tiles past the end of the list repeat the last one (their logits are never used); a partial last
-// key block is masked in the last step, which is the only one that applies key counts.
+// key block is masked in the last step (the last two with 128-key blocks), the only ones that apply key counts.
+// Listed blocks of 128 keys are walked as two tiles, listed blocks of 32 keys are paired up two to a tile
+// (see the notes at `tile_shift` / `half_blocks` below).
 #include "kernels.hpp"
 #include "tile_bf16.hpp"
 

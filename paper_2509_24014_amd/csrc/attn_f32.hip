@@ -70,7 +70,7 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a) {
       key0 = t * kTileKF;
     }
     // keys of this tile that exist: fewer than 32 only at the end of a sequence whose length is not a
-    // multiple of the tile; a tile wholly past the end (second half of a partial 64-key block) is skipped
+    // multiple of the tile; a tile wholly past the end (the later tiles of a partial key block) is skipped
     const int valid = L - key0 < kTileKF ? L - key0 : kTileKF;
     if (valid <= 0) continue;  // uniform over the work-group
     __syncthreads();  // everyone is done reading the previous tile

@@ -34,7 +34,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int kTileK = 64;  // keys per K/V tile of the bf16 kernels (= block_k)
+constexpr int kTileK = 64;  // keys per K/V tile of the bf16 kernels (a listed key block is half a tile, one tile or two)
 
 #define SPARSED_LDS __attribute__((address_space(3)))
 #define SPARSED_GLOBAL __attribute__((address_space(1)))
