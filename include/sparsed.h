@@ -109,7 +109,10 @@ typedef struct sparsed_exec {
  *    sparsed_kept_blocks(rho, that many) per query block: row_ptr[I] = I * k_b for its ceil(len / block_q)
  *    query blocks, and the query blocks it does not have get empty rows. pooled_out entries of blocks a
  *    sample does not have are not written. nqb, nkb and cap_per_head are still those of L.
- *  - A length <= 0 makes the whole sample a no-op. The isolated-selection entry points do not take
+ *  - select_pattern_isolated: the same with two ranges per sample, [0, min(prefill_blocks, its blocks)) and
+ *    the rest of its blocks, each with its own count; a sample no longer than the prefill has one range.
+ *  - A length <= 0 makes the whole sample a no-op. A prefill boundary INSIDE a key block
+ *    (select_pattern_isolated_tokens with prefill_tokens not a multiple of block_k) does not go with
  *    per-sample lengths (SPARSED_ERR_UNSUPPORTED).
  */
 

@@ -248,9 +248,10 @@ def select_pattern(q, k, block_q: int, block_k: int, rho: float, lse_in=None, wo
 
 
 def select_pattern_isolated(q, k, block_q: int, block_k: int, rho: float, prefill_blocks: int, lse_in=None, workspace=None,
-                            pooled_out=None, index: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
+                            pooled_out=None, index: Optional[BlockIndex] = None, stream=None,
+                            seq_lens: Optional[torch.Tensor] = None) -> BlockIndex:
     """sparsed_select_pattern_isolated: separate top-rho% over prefill and generation key blocks."""
-    return _select(q, k, block_q, block_k, rho, int(prefill_blocks), lse_in, workspace, pooled_out, index, stream)
+    return _select(q, k, block_q, block_k, rho, int(prefill_blocks), lse_in, workspace, pooled_out, index, stream, seq_lens=seq_lens)
 
 
 def select_pattern_isolated_tokens(q, k, block_q: int, block_k: int, rho: float, prefill_tokens: int, lse_in=None,

@@ -337,18 +337,25 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
     const int len = a.seq_lens[bh / a.heads_per_batch];
     const int L = len < a.L ? len : a.L;
     const int nkb_b = L > 0 ? (L + a.block_k - 1) / a.block_k : 0, nqb_b = L > 0 ? (L + a.block_q - 1) / a.block_q : 0;
-    int keep_b = 0;
-    if (nkb_b > 0) {  // the host's count rule, in the same double arithmetic
-      double x = ceil(a.rho * (double)nkb_b - 1e-9);
+    auto kept = [&](int nblocks) -> int {  // the host's count rule, in the same double arithmetic
+      if (nblocks <= 0) return 0;
+      double x = ceil(a.rho * (double)nblocks - 1e-9);
       if (!(x >= 1.0)) x = 1.0;
-      if (x > (double)nkb_b) x = (double)nkb_b;
-      keep_b = (int)x;
-    }
+      if (x > (double)nblocks) x = (double)nblocks;
+      return (int)x;
+    };
+    // With a prefill / generation split (Eq. 5) the sample's two ranges are [0, split) and [split, nkb_b), the
+    // first cut to the blocks the sample has; a sample no longer than the prefill has one range only.
+    const int split_b = a.split < nkb_b ? a.split : nkb_b;
+    const int keep_lo_b = kept(split_b), keep_hi_b = kept(nkb_b - split_b);
+    const int keep_b = keep_lo_b + keep_hi_b;
     int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1);
     if (I < nqb_b) {
       for (int J = lane; J < nkb_b; J += 64) row[J] = src[J];
       __syncthreads();
-      emit_topk_range(row, 0, nkb_b, keep_b, a.col_idx + (int64_t)bh * a.cap_per_head + (int64_t)I * keep_b, lane);
+      int32_t* out_b = a.col_idx + (int64_t)bh * a.cap_per_head + (int64_t)I * keep_b;
+      emit_topk_range(row, 0, split_b, keep_lo_b, out_b, lane);
+      emit_topk_range(row, split_b, nkb_b, keep_hi_b, out_b + keep_lo_b, lane);
     }
     if (lane == 0) {
       rp[I] = (I < nqb_b ? I : nqb_b) * keep_b;  // query blocks the sample does not have get empty rows

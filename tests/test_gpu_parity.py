@@ -502,6 +502,46 @@ def test_per_sample_lengths(dtype, bq, bk, L, D, lens, rho):
         assert_output_close(out_s[b:b + 1, :, :n], want, dtype, f"sparse sample {b}")
 
 
+@pytest.mark.parametrize("dtype,bq,bk,L,D,lens,pblocks,rho", [
+    (torch.bfloat16, 128, 64, 1024, 128, [1024, 700, 200, 129, 64], 4, 0.3),   # prefill of 4 key blocks; two samples no longer than it
+    (torch.bfloat16, 64, 128, 1000, 64, [1000, 500, 257], 2, 0.4),
+    (torch.float32, 32, 32, 256, 64, [256, 100, 33, 20], 3, 0.5),
+])
+def test_isolated_selection_with_per_sample_lengths(dtype, bq, bk, L, D, lens, pblocks, rho):
+    """Isolated selection in a padded batch: every sample ranks its prefill blocks [0, p) and its generation blocks
+    [p, nkb_b) separately, as if passed alone; a sample no longer than the prefill has one range only."""
+    B, H = len(lens), 2
+    q, k, v = _rand_qkv(B, H, H, L, D, dtype, seed=L + 3 * D, scale=1.0 if dtype == torch.float32 and D == 64 else 0.5)
+    qd, kd, vd = _dev(q, k, v)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    ix = sd.select_pattern_isolated(qd, kd, bq, bk, rho, pblocks, seq_lens=sl)
+    sd.index_validate(ix)
+    out_s = torch.full((B, H, L, D), 7.0, dtype=dtype, device=DEV)
+    sd.attn_sparse(qd, kd, vd, ix, out=out_s, seq_lens=sl)
+    torch.cuda.synchronize()
+    rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+    for b, n in enumerate(lens):
+        qb, kb, vb = q[b:b + 1, :, :n], k[b:b + 1, :, :n], v[b:b + 1, :, :n]
+        nqb_b, nkb_b = -(-n // bq), -(-n // bk)
+        n_pre = min(pblocks, nkb_b)
+        apool = oracle.pool_scores(qb, kb, bq, bk)
+        rp_o, ci_o = oracle.select_isolated(apool, rho, n_pre)
+        k_lo, k_hi = oracle.kept_blocks(rho, n_pre), (oracle.kept_blocks(rho, nkb_b - n_pre) if nkb_b > n_pre else 0)
+        keep = k_lo + k_hi
+        for h in range(H):
+            assert rp[b, h, :nqb_b + 1].tolist() == rp_o[0, h].tolist()
+            assert (rp[b, h, nqb_b:] == nqb_b * keep).all()
+            got = ci[b, h, :nqb_b * keep].reshape(nqb_b, keep)
+            want = ci_o[0, h].reshape(nqb_b, keep)
+            compare_index(got[:, :k_lo].reshape(-1), want[:, :k_lo].reshape(-1), apool[0, h][:, :n_pre], k_lo)
+            if k_hi:
+                compare_index(got[:, k_lo:].reshape(-1) - n_pre, want[:, k_lo:].reshape(-1) - n_pre, apool[0, h][:, n_pre:], k_hi)
+        rp_b = rp[b:b + 1, :, :nqb_b + 1].copy()
+        want = oracle.attn_sparse(qb, kb, vb, rp_b, ci[b:b + 1], bq, bk)
+        assert_output_close(out_s[b:b + 1, :, :n], want, dtype, f"sparse sample {b}")
+        assert (out_s[b, :, n:] == 7.0).all()
+
+
 # ----------------------------------------------------------------------------- seeded sweep over the parameter space
 def _sweep_cases(n, seed):
     rng = np.random.default_rng(seed)
