@@ -7,8 +7,9 @@
 // double-buffered, one barrier per tile (tile_bf16.hpp).
 //
 // Software pipeline inside every wave. On this chip a matrix instruction runs in the background
-// of the wave that issued it while that same wave keeps issuing vector instructions, but matrix
-// work of one wave and vector work of ANOTHER wave on the same SIMD get in each other's way. So
+// of the wave that issued it while that same wave keeps issuing vector instructions, whereas two
+// waves of a SIMD that each run a matrix block and then a vector block drift into doing the same
+// kind of work at the same time. So
 // a wave works in sub-steps of 32 keys, and sub-step u interleaves, in one instruction stream,
 //      matrix:  O += P(u-1) V(u-1)   and   S(u+1) = K(u+1) Q^T
 //      vector:  online softmax of S(u)  ->  P(u), running max / sum
