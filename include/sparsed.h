@@ -14,13 +14,20 @@
  *    returns. Descriptor structs themselves live in HOST memory.
  *  - Work is enqueued on `ex->stream` (a hipStream_t; NULL or ex == NULL means
  *    the default stream) and the call returns without synchronising, except
- *    where a function says it synchronises. sparsed_attn_dense,
- *    sparsed_attn_sparse and, given a workspace, the selection entry points
+ *    where a function says it synchronises. The library allocates no device
+ *    memory and keeps no state between calls except the thread-local error
+ *    message: scratch memory is the caller's (`ex->workspace`), and a call that
+ *    needs one and is given none returns SPARSED_ERR_WORKSPACE.
+ *    sparsed_attn_dense, sparsed_attn_sparse and the selection entry points
  *    only launch kernels (no allocation, no memset, no copy), so they may be
  *    recorded into a HIP graph on a capturing stream.
- *  - Errors are returned as a sparsed_status; nothing throws or aborts. On any
- *    status other than SPARSED_OK no kernel was launched and outputs are
- *    untouched. sparsed_last_error() gives a thread-local message.
+ *  - Errors are returned as a sparsed_status; nothing throws or aborts. Every
+ *    argument check happens before the first launch: on a status other than
+ *    SPARSED_OK and SPARSED_ERR_HIP no kernel was launched and outputs are
+ *    untouched. SPARSED_ERR_HIP reports a failed launch; the selection entry
+ *    points launch several kernels in a row, so earlier ones of the same call
+ *    may already be enqueued (they write only the workspace, pooled_out and
+ *    the index). sparsed_last_error() gives a thread-local message.
  *  - Tensors are [B, H, L, D] views with arbitrary element strides for B, H, L
  *    and unit stride for D. `data` must be 16-byte aligned and every stride a
  *    multiple of 8 elements (bf16) or 4 elements (fp32), so that every row is
@@ -92,7 +99,7 @@ typedef struct sparsed_block_index {
 /* Optional execution context. A NULL context means: default stream, no extras. */
 typedef struct sparsed_exec {
   void* stream;           /* hipStream_t */
-  void* workspace;        /* device scratch for sparsed_select_pattern, 256-byte aligned */
+  void* workspace;        /* device scratch for the selection calls and sparsed_index_validate, 256-byte aligned */
   size_t workspace_bytes; /* its size */
   float* lse_out;         /* attn_dense: optional [B, Hq, L] fp32, log-sum-exp of each row's scaled logits */
   const float* lse_in;    /* select_pattern: optional [B, Hq, L] fp32 from attn_dense on the SAME q, k */
@@ -138,11 +145,10 @@ sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor*
  * The L x L matrix A is never formed. Fills out_block_index->row_ptr / col_idx
  * (every row has exactly k entries, row_ptr[I] = I*k); its B, H, nqb, nkb,
  * block_q, block_k must already describe q and the blocks and cap_per_head must
- * be >= nqb*k, else SPARSED_ERR_INDEX. Needs a workspace of
- * sparsed_select_workspace_bytes(); if ex or ex->workspace is NULL the library
- * uses a device buffer of its own, allocated (synchronously) on first use and
- * kept for the life of the process; calls that rely on it must not overlap on one
- * GPU (they would share it), so callers with several streams pass their own.
+ * be >= nqb*k, else SPARSED_ERR_INDEX. Needs ex->workspace of at least
+ * sparsed_select_workspace_bytes() bytes (SPARSED_ERR_WORKSPACE otherwise); the
+ * workspace holds the row statistics and the pooled scores while the call's
+ * kernels run, so calls that may overlap on the GPU need a workspace each.
  */
 sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_tensor* k,
                                       int32_t block_q, int32_t block_k, double rho,
@@ -232,20 +238,10 @@ size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t bl
 /*
  * Checks on the device that every row of the index is in range, strictly
  * ascending and within cap_per_head. SYNCHRONISES the stream. Returns
- * SPARSED_ERR_INDEX if any row is malformed.
+ * SPARSED_ERR_INDEX if any row is malformed. Needs ex->workspace of at least
+ * 256 bytes (its first word counts the malformed rows).
  */
 sparsed_status sparsed_index_validate(const sparsed_block_index* idx, const sparsed_exec* ex);
-
-/*
- * Diagnostic, not part of the method: the rate (TFLOP/s) this GPU sustains on bf16 32x32x16 matrix
- * instructions alone, operands in registers, 8 waves on every compute unit for `iters` x 32
- * instructions per wave. random_operands == 0 uses all-zero operands (reaches the published peak);
- * != 0 uses operands with random signs and mantissas, for which the chip settles at a lower clock:
- * the practical ceiling for kernels that multiply real data. SYNCHRONISES the stream. Uses
- * ex->workspace (512 KiB) if given, else the library's own buffer.
- */
-sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out,
-                                       const sparsed_exec* ex);
 
 const char* sparsed_status_string(sparsed_status s);
 const char* sparsed_last_error(void); /* thread-local, never NULL */

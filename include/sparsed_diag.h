@@ -1,0 +1,31 @@
+/*
+ * sparsed_diag.h - diagnostics of the MI355X (gfx950) SparseD attention library.
+ *
+ * Nothing here is part of the method (arXiv 2509.24014) or of the hot path: these calls measure the
+ * machine, for reports that put the attention kernels' rates next to what the hardware sustains.
+ * Same conventions as sparsed.h (C11, device pointers owned by the caller, status codes).
+ */
+#ifndef SPARSED_DIAG_H
+#define SPARSED_DIAG_H
+
+#include "sparsed.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * The rate (TFLOP/s) this GPU sustains on bf16 32x32x16 matrix instructions alone, operands in
+ * registers, 8 waves on every compute unit for `iters` x 32 instructions per wave (iters in
+ * [1, 1000000]). random_operands == 0 uses all-zero operands (reaches the published peak); != 0 uses
+ * operands with random signs and mantissas, for which the chip settles at a lower clock: the
+ * practical ceiling for kernels that multiply real data. SYNCHRONISES the stream. Needs
+ * ex->workspace of at least 512 KiB (SPARSED_ERR_WORKSPACE otherwise).
+ */
+sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out,
+                                       const sparsed_exec* ex);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSED_DIAG_H */

@@ -224,6 +224,10 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
         raise ValueError("pooled_out must be contiguous fp32 [B, Hq, nqb, nkb]")
     if lse_in is not None and (lse_in.dtype != torch.float32 or not lse_in.is_contiguous() or lse_in.numel() != B * H * L):
         raise ValueError("lse_in must be contiguous fp32 [B, Hq, L]")
+    if stream is not None and int(stream.cuda_stream) != int(torch.cuda.current_stream(q.device).cuda_stream):
+        # the kernels run on `stream`; keep the allocator from handing these blocks to later work on the current stream
+        for t in (workspace, index.row_ptr, index.col_idx):
+            t.record_stream(stream)
     ex = _Exec(_stream_ptr(stream), workspace.data_ptr(), workspace.numel() * workspace.element_size(), None,
                lse_in.data_ptr() if lse_in is not None else None, pooled_out.data_ptr() if pooled_out is not None else None,
                _seq_lens_ptr(seq_lens, B))
@@ -274,9 +278,11 @@ def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, 
 
 
 def probe_mfma_bf16(random_operands: bool, iters: int = 20000) -> float:
-    """sparsed_probe_mfma_bf16: sustained TFLOP/s of bf16 matrix instructions alone (diagnostic)."""
+    """sparsed_probe_mfma_bf16: sustained TFLOP/s of bf16 matrix instructions alone (diagnostic, synchronises)."""
     out = ctypes.c_double(0.0)
-    _check(load_library().sparsed_probe_mfma_bf16(1 if random_operands else 0, iters, ctypes.byref(out), None))
+    ws = torch.empty(512 * 1024, dtype=torch.uint8, device="cuda")
+    ex = _Exec(_stream_ptr(None), ws.data_ptr(), ws.numel(), None, None, None, None)
+    _check(load_library().sparsed_probe_mfma_bf16(1 if random_operands else 0, iters, ctypes.byref(out), ctypes.byref(ex)))
     return out.value
 
 
@@ -302,6 +308,7 @@ def index_fill_window(B: int, H: int, seq_len: int, block_q: int, block_k: int, 
 def index_validate(index: BlockIndex, stream=None) -> None:
     """sparsed_index_validate: raises SparsedError if any row is malformed (synchronises)."""
     lib = load_library()
-    ex = _Exec(_stream_ptr(stream), None, 0, None, None, None)
+    flag = torch.empty(256, dtype=torch.uint8, device=index.row_ptr.device)   # the call synchronises before it returns
+    ex = _Exec(_stream_ptr(stream), flag.data_ptr(), flag.numel(), None, None, None, None)
     ci = index._c()
     _check(lib.sparsed_index_validate(ctypes.byref(ci), ctypes.byref(ex)))

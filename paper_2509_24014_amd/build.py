@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparsed.so")
 SOURCES = ["api.hip", "attn_bf16.hip", "attn_bf16_splitk.hip", "attn_f32.hip", "select.hip", "probe.hip"]
-HEADERS = ["kernels.hpp", "tile_bf16.hpp", "tile_f32.hpp", os.path.join("..", "..", "include", "sparsed.h")]
+HEADERS = ["kernels.hpp", "tile_bf16.hpp", "tile_f32.hpp", os.path.join("..", "..", "include", "sparsed.h"),
+           os.path.join("..", "..", "include", "sparsed_diag.h")]
 # packed fp32 VALU forms are disabled on purpose: some of their encodings have given silently wrong results on this chip
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -4,9 +4,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <mutex>
 
 #include "../../include/sparsed.h"
+#include "../../include/sparsed_diag.h"
 #include "kernels.hpp"
 
 using namespace sparsed;
@@ -70,8 +70,7 @@ sparsed_status check_out(const sparsed_tensor* q, const sparsed_tensor* out) {
 
 sparsed_status check_blocks(const sparsed_tensor* q, int bq, int bk) {
   if (bq != 32 && bq != 64 && bq != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_q %d not in {32,64,128}", bq);
-  if (q->dtype == SPARSED_BF16 && bk != 32 && bk != 64 && bk != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64,128} (bf16)", bk);
-  if (q->dtype == SPARSED_F32 && bk != 32 && bk != 64 && bk != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64,128}", bk);
+  if (bk != 32 && bk != 64 && bk != 128) return fail(SPARSED_ERR_UNSUPPORTED, "block_k %d not in {32,64,128}", bk);
   return SPARSED_OK;
 }
 
@@ -92,30 +91,12 @@ TensorArg targ(const sparsed_tensor* t) { return TensorArg{t->data, t->stride_b,
 
 float scale_log2(int D) { return (float)(1.4426950408889634 / std::sqrt((double)D)); }
 
-// Library-owned fallback workspace for callers that pass none: one growing buffer per device.
-std::mutex g_ws_mu;
-void* g_ws[64] = {};
-size_t g_ws_bytes[64] = {};
-
-sparsed_status own_workspace(size_t need, void** out) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-  if (dev < 0 || dev >= 64) return fail(SPARSED_ERR_HIP, "device ordinal %d out of range", dev);
-  std::lock_guard<std::mutex> lk(g_ws_mu);
-  if (g_ws_bytes[dev] < need) {
-    if (g_ws[dev]) {
-      e = hipDeviceSynchronize();  // earlier calls may still be using the old buffer
-      if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
-      (void)hipFree(g_ws[dev]);
-      g_ws[dev] = nullptr;
-      g_ws_bytes[dev] = 0;
-    }
-    e = hipMalloc(&g_ws[dev], need);
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
-    g_ws_bytes[dev] = need;
-  }
-  *out = g_ws[dev];
+// The caller's workspace, checked: present, large enough, 256-byte aligned.
+sparsed_status caller_workspace(const sparsed_exec* ex, size_t need, const char* what, char** out) {
+  if (!ex || !ex->workspace) return fail(SPARSED_ERR_WORKSPACE, "%s needs ex->workspace (%zu bytes)", what, need);
+  if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "%s: workspace %zu bytes < %zu needed", what, ex->workspace_bytes, need);
+  if (reinterpret_cast<uintptr_t>(ex->workspace) % 256) return fail(SPARSED_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", what);
+  *out = static_cast<char*>(ex->workspace);
   return SPARSED_OK;
 }
 
@@ -173,7 +154,7 @@ sparsed_status attention(Mode mode, const sparsed_tensor* q, const sparsed_tenso
 // strictly inside a key block (prefill_blocks is then ignored).
 sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int32_t bq, int32_t bk, double rho,
                            int32_t prefill_blocks, bool isolated, sparsed_block_index* ix, const sparsed_exec* ex,
-                           int32_t boundary_token = -1) {
+                           int32_t boundary_token = -1, char* fixed_scratch = nullptr, size_t fixed_scratch_bytes = 0) {
   sparsed_status st;
   if ((st = check_tensor(q, "q")) || (st = check_tensor(k, "k")) || (st = check_qk(q, k, "k"))) return st;
   if ((st = check_blocks(q, bq, bk))) return st;
@@ -210,14 +191,12 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   const size_t base_bytes = select_ws_bytes(q->B, q->H, q->L, nqb, nkb);
   const size_t need = base_bytes + (straddle >= 0 ? select_tokens_extra_bytes(q->B, q->H, nqb, nkb) : 0);
   char* ws = nullptr;
-  if (ex && ex->workspace) {
-    if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ex->workspace_bytes, need);
-    if (reinterpret_cast<uintptr_t>(ex->workspace) % 256) return fail(SPARSED_ERR_WORKSPACE, "workspace is not 256-byte aligned");
-    ws = static_cast<char*>(ex->workspace);
-  } else {
-    void* p = nullptr;
-    if ((st = own_workspace(need, &p))) return st;
-    ws = static_cast<char*>(p);
+  if (fixed_scratch) {  // the allocation-free entry point: scratch of a fixed size that lives in the library's code object
+    if (need > fixed_scratch_bytes)
+      return fail(SPARSED_ERR_WORKSPACE, "selection needs %zu bytes of scratch, the built-in buffer holds %zu", need, fixed_scratch_bytes);
+    ws = fixed_scratch;
+  } else if ((st = caller_workspace(ex, need, "pattern selection", &ws))) {
+    return st;
   }
   float* lse_buf = reinterpret_cast<float*>(ws);
   float* apool = (ex && ex->pooled_out) ? ex->pooled_out : reinterpret_cast<float*>(ws + lse_bytes);
@@ -386,19 +365,19 @@ sparsed_status sparsed_index_validate(const sparsed_block_index* ix, const spars
   if (!ix->row_ptr || !ix->col_idx) return fail(SPARSED_ERR_NULL, "block index row_ptr / col_idx is NULL");
   if (ix->B <= 0 || ix->H <= 0 || ix->nqb <= 0 || ix->nkb <= 0 || ix->cap_per_head < 0)
     return fail(SPARSED_ERR_INDEX, "block index has non-positive dimensions");
+  char* ws = nullptr;
+  const sparsed_status st = caller_workspace(ex, 256, "index validation", &ws);
+  if (st != SPARSED_OK) return st;
   hipStream_t s = stream_of(ex);
-  int32_t* bad = nullptr;
-  hipError_t e = hipMalloc(&bad, sizeof(int32_t));
-  if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+  int32_t* bad = reinterpret_cast<int32_t*>(ws);  // device counter of malformed rows
   int32_t host_bad = 0;
-  e = hipMemcpyAsync(bad, &host_bad, sizeof(int32_t), hipMemcpyHostToDevice, s);
+  hipError_t e = hipMemsetAsync(bad, 0, sizeof(int32_t), s);
   if (e == hipSuccess) {
     ValidateArgs a{ix->row_ptr, ix->col_idx, ix->B * ix->H * ix->nqb, ix->nqb, ix->nkb, ix->cap_per_head, bad};
     e = launch_validate(a, s);
   }
   if (e == hipSuccess) e = hipMemcpyAsync(&host_bad, bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
-  (void)hipFree(bad);
   if (e != hipSuccess) return hip_fail(e, "index validation");
   if (host_bad != 0) return fail(SPARSED_ERR_INDEX, "%d malformed rows in the block index", host_bad);
   return SPARSED_OK;
@@ -443,22 +422,16 @@ int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t b
 sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out, const sparsed_exec* ex) {
   if (!tflops_out) return fail(SPARSED_ERR_NULL, "tflops_out is NULL");
   if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
-  void* scratch = nullptr;
-  const size_t need = (size_t)kProbeFloats * sizeof(float);
-  if (ex && ex->workspace) {
-    if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "probe needs %zu bytes of workspace", need);
-    scratch = ex->workspace;
-  } else {
-    const sparsed_status st = own_workspace(need, &scratch);
-    if (st != SPARSED_OK) return st;
-  }
+  char* scratch = nullptr;
+  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "matrix-core rate probe", &scratch);
+  if (st != SPARSED_OK) return st;
   hipStream_t s = stream_of(ex);
   hipEvent_t t0 = nullptr, t1 = nullptr;
   hipError_t e = hipEventCreate(&t0);
   if (e == hipSuccess) e = hipEventCreate(&t1);
-  if (e == hipSuccess) e = launch_mfma_rate(static_cast<float*>(scratch), iters / 8 + 1, random_operands, s);  // warm-up
+  if (e == hipSuccess) e = launch_mfma_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, random_operands, s);  // warm-up
   if (e == hipSuccess) e = hipEventRecord(t0, s);
-  if (e == hipSuccess) e = launch_mfma_rate(static_cast<float*>(scratch), iters, random_operands, s);
+  if (e == hipSuccess) e = launch_mfma_rate(reinterpret_cast<float*>(scratch), iters, random_operands, s);
   if (e == hipSuccess) e = hipEventRecord(t1, s);
   if (e == hipSuccess) e = hipEventSynchronize(t1);
   float ms = 0.f;

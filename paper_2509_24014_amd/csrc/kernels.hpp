@@ -1,4 +1,4 @@
-// Internal interface between the host-side C ABI (api.cpp) and the gfx950 kernels.
+// Internal interface between the host-side C ABI (api.hip) and the gfx950 kernels.
 // Not installed; include/sparsed.h is the public boundary.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -128,7 +128,6 @@ __host__ __device__ inline int window_row_length(int I, int block_q, int block_k
 constexpr int kProbeGroups = 256;
 constexpr int kProbeFloats = kProbeGroups * 512;
 hipError_t launch_mfma_rate(float* scratch, int iters, int random_operands, hipStream_t s);
-hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
 
 // Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).
 int dense_qtile_bf16(int L);

@@ -15,9 +15,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "sparsed.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sparsed_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(sparsed_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -85,6 +89,11 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_select_pattern(R(qb), R(qb), 64, 16, 0.3, R(_ix(nqb=4, nkb=16, bq=64, bk=16)), None) == 6   # bf16 bk
     ex = binding._Exec(None, 0x4000, 16, None, None, None)
     assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(ix), R(ex)) == 7          # workspace too small
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(ix), None) == 7           # no workspace: the library has none of its own
+    assert b"workspace" in lib.sparsed_last_error()
+    assert lib.sparsed_select_pattern(R(q), R(k), 32, 32, 0.3, R(ix), R(binding._Exec(None, 0x4010, 1 << 20, None, None, None))) == 7   # misaligned
+    assert lib.sparsed_index_validate(R(ix), None) == 7
+    assert lib.sparsed_index_validate(R(ix), R(ex)) == 7
     assert lib.sparsed_attn_sparse(R(q), R(k), R(v), None, R(o), None) == 1
     assert lib.sparsed_attn_sparse(R(q), R(k), R(v), R(_ix(H=4)), R(o), None) == 8
     assert lib.sparsed_select_pattern_isolated(R(q), R(k), 32, 32, 0.3, 9, R(_ix(cap=64)), None) == 5
@@ -92,12 +101,14 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=64)), R(exl)) == 6  # boundary inside a block + per-sample lengths
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 300, R(_ix(cap=64)), None) == 5   # boundary past L
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=8)), None) == 8    # capacity
+    assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=64)), None) == 7   # workspace
     assert lib.sparsed_index_fill_window(R(_ix(cap=4)), 256, 64, 0, None) == 8                                   # capacity
     assert lib.sparsed_index_fill_window(R(_ix()), 300, 64, 0, None) == 8                                        # 8 blocks do not describe 300 tokens
     assert lib.sparsed_index_window_entries(256, 32, 32, 0, 0) == 8
     out = ctypes.c_double(0.0)
     assert lib.sparsed_probe_mfma_bf16(1, 0, ctypes.byref(out), None) == 5                                       # iters
     assert lib.sparsed_probe_mfma_bf16(1, 10, None, None) == 1
+    assert lib.sparsed_probe_mfma_bf16(1, 10, ctypes.byref(out), None) == 7                                       # workspace
     assert lib.sparsed_status_string(8) == b"malformed block index"
 
 
