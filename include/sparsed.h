@@ -156,6 +156,27 @@ sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_ten
                                       const sparsed_exec* ex);
 
 /*
+ * sparsed_select_pattern for callers that cannot allocate device memory or bring a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * selection, same kernels and results, with the scratch (row statistics + pooled scores) in a
+ * fixed array of SPARSED_STATIC_SCRATCH_BYTES that is part of the library's code object; each GPU
+ * the library runs on holds its own copy until the process ends. ex->workspace is ignored;
+ * ex->stream, lse_in, pooled_out and seq_lens work as in sparsed_select_pattern. The call
+ * allocates and frees nothing (its first call on a device looks the array's device address up
+ * once). Returns SPARSED_ERR_WORKSPACE when sparsed_select_workspace_bytes() for these arguments
+ * exceeds SPARSED_STATIC_SCRATCH_BYTES (e.g. 32 heads of 65536 tokens with 128 x 64 blocks need
+ * 75 MB; 32 heads of 16384 tokens with 64 x 64 blocks need 10 MB and fit). All calls on one GPU
+ * share that GPU's array, which keeps the previous call's contents (every entry a call reads it
+ * has written first): calls that may overlap on one GPU race, so keep them on one stream or
+ * order them with events.
+ */
+#define SPARSED_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+sparsed_status sparsed_select_pattern_static(const sparsed_tensor* q, const sparsed_tensor* k,
+                                             int32_t block_q, int32_t block_k, double rho,
+                                             sparsed_block_index* out_block_index,
+                                             const sparsed_exec* ex);
+
+/*
  * Sparse attention of the later steps ("Sparse Reusing"; Eq. 3 with the mask of
  * Eq. 4): rows of query block I attend only to the keys of the key blocks
  * listed for I (those below L, for a partial last block); the softmax is

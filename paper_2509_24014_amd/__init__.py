@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     select_pattern,
     select_pattern_isolated,
     select_pattern_isolated_tokens,
+    select_pattern_static,
+    STATIC_SCRATCH_BYTES,
     select_workspace_bytes,
     version,
 )

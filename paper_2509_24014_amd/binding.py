@@ -25,6 +25,7 @@ EXPORTS = [
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
     "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16",
     "sparsed_select_pattern_isolated_tokens", "sparsed_select_tokens_workspace_bytes",
+    "sparsed_select_pattern_static",
 ]
 
 
@@ -72,6 +73,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_attn_dense.restype = ctypes.c_int
     lib.sparsed_select_pattern.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, I, E]
     lib.sparsed_select_pattern.restype = ctypes.c_int
+    lib.sparsed_select_pattern_static.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, I, E]
+    lib.sparsed_select_pattern_static.restype = ctypes.c_int
     lib.sparsed_select_pattern_isolated.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, I, E]
     lib.sparsed_select_pattern_isolated.restype = ctypes.c_int
     lib.sparsed_select_pattern_isolated_tokens.argtypes = [T, T, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, I, E]
@@ -249,6 +252,22 @@ def select_pattern(q, k, block_q: int, block_k: int, rho: float, lse_in=None, wo
                    index: Optional[BlockIndex] = None, stream=None, seq_lens: Optional[torch.Tensor] = None) -> BlockIndex:
     """sparsed_select_pattern: pooled post-softmax scores + per-row top-k -> CSR block index."""
     return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, seq_lens=seq_lens)
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def select_pattern_static(q, k, block_q: int, block_k: int, rho: float, index: BlockIndex, lse_in=None, pooled_out=None,
+                          stream=None, seq_lens: Optional[torch.Tensor] = None) -> BlockIndex:
+    """sparsed_select_pattern_static: selection with the library's built-in scratch; allocates nothing (the caller
+    brings the index to fill)."""
+    lib = load_library()
+    ex = _Exec(_stream_ptr(stream), None, 0, None, lse_in.data_ptr() if lse_in is not None else None,
+               pooled_out.data_ptr() if pooled_out is not None else None, _seq_lens_ptr(seq_lens, q.shape[0]))
+    tq, tk, ci = _tensor(q, "q"), _tensor(k, "k"), index._c()
+    _check(lib.sparsed_select_pattern_static(ctypes.byref(tq), ctypes.byref(tk), block_q, block_k, float(rho), ctypes.byref(ci),
+                                             ctypes.byref(ex)))
+    return index
 
 
 def select_pattern_isolated(q, k, block_q: int, block_k: int, rho: float, prefill_blocks: int, lse_in=None, workspace=None,

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/sparsed.h"
 #include "../../include/sparsed_diag.h"
@@ -97,6 +98,34 @@ sparsed_status caller_workspace(const sparsed_exec* ex, size_t need, const char*
   if (ex->workspace_bytes < need) return fail(SPARSED_ERR_WORKSPACE, "%s: workspace %zu bytes < %zu needed", what, ex->workspace_bytes, need);
   if (reinterpret_cast<uintptr_t>(ex->workspace) % 256) return fail(SPARSED_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", what);
   *out = static_cast<char*>(ex->workspace);
+  return SPARSED_OK;
+}
+
+// Scratch of the allocation-free selection entry point: a fixed-size array inside the library's code
+// object, one copy per GPU at its own address, held until the process ends. Host code never uses the
+// array's name as an address: fixed_scratch() asks the runtime for the device address once per device
+// (with that device current) and hands that pointer to the kernels like any caller's workspace.
+constexpr size_t kFixedScratchBytes = SPARSED_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kFixedScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+sparsed_status fixed_scratch(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(SPARSED_ERR_HIP, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || reinterpret_cast<uintptr_t>(p) % 256) return fail(SPARSED_ERR_HIP, "built-in scratch buffer has no usable device address");
+    g_scratch_ptr[dev] = static_cast<char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
   return SPARSED_OK;
 }
 
@@ -314,6 +343,14 @@ sparsed_status sparsed_attn_sparse(const sparsed_tensor* q, const sparsed_tensor
 sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q, int32_t block_k, double rho,
                                       sparsed_block_index* out_block_index, const sparsed_exec* ex) {
   return select_impl(q, k, block_q, block_k, rho, 0, false, out_block_index, ex);
+}
+
+sparsed_status sparsed_select_pattern_static(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q, int32_t block_k,
+                                             double rho, sparsed_block_index* out_block_index, const sparsed_exec* ex) {
+  char* ws = nullptr;
+  const sparsed_status st = fixed_scratch(&ws);
+  if (st != SPARSED_OK) return st;
+  return select_impl(q, k, block_q, block_k, rho, 0, false, out_block_index, ex, -1, ws, kFixedScratchBytes);
 }
 
 sparsed_status sparsed_select_pattern_isolated(const sparsed_tensor* q, const sparsed_tensor* k, int32_t block_q, int32_t block_k,
