@@ -32,14 +32,30 @@ def _flops(cfg, keep):
     return dense, select, sparse
 
 
+def _kernel_source_digest():
+    """sha256 (first 16 hex digits) over the sources of the attention kernels: what a counter run was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("attn_bf16.hip", "tile_bf16.hpp", "kernels.hpp"):
+        with open(os.path.join(ROOT, "paper_2509_24014_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def _traffic_from_profiles(workload_name):
-    """HBM bytes per launch of the sparse kernel from the committed counter summary, if there is one."""
+    """HBM bytes per launch of the sparse kernel from the committed counter summary (FETCH_SIZE / WRITE_SIZE runs
+    cannot be taken inside this process), with the digest of the kernel sources it was measured on: a figure taken
+    on other sources than the ones running now is reported as stale, not as this run's traffic."""
     path = os.path.join(ROOT, "profiles", f"attn_sparse_{workload_name}_hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get("traffic_bytes_per_launch")
+            rec = json.load(f)
     except Exception:
-        return None
+        return None, None
+    now = _kernel_source_digest()
+    info = {"file": os.path.relpath(path, ROOT), "measured_on_sources": rec.get("kernel_source_digest"),
+            "sources_now": now, "stale": rec.get("kernel_source_digest") != now}
+    return (None if info["stale"] else rec.get("traffic_bytes_per_launch")), info
 
 
 def cpu_baseline(cfg, q, k, v, index, keep, budget_s=15.0):
@@ -141,6 +157,69 @@ def _select_bytes(cfg, keep):
     return qk + lse + index
 
 
+def per_workload_block(sd, workload, torch, names, seed, peak):
+    """Per-call times of the other named workloads (not the headline step; each timed with HIP events on the launch
+    stream after a warm-up call), and the whole T-step schedule where the workload has one."""
+    dev = torch.device("cuda:0")
+
+    def timed(fn, reps):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    block = {}
+    for name in names:
+        cfg = workload.get_config(name)
+        keep = sd.kept_blocks(cfg.rho, cfg.nkb)
+        inp = workload.make_inputs(cfg, seed=seed, device=dev)
+        q, k, v = inp.rounded()
+        out = torch.empty_like(q)
+        lse = torch.empty(cfg.B, cfg.Hq, cfg.L, dtype=torch.float32, device=dev)
+        ws = torch.empty(sd.select_workspace_bytes(q, cfg.bq, cfg.bk), dtype=torch.uint8, device=dev)
+        index = sd.BlockIndex(torch.empty(cfg.B, cfg.Hq, cfg.nqb + 1, dtype=torch.int32, device=dev),
+                              torch.empty(cfg.B, cfg.Hq, cfg.nqb * keep, dtype=torch.int32, device=dev), cfg.bq, cfg.bk, cfg.nkb)
+        reps = 20 if cfg.L <= 16384 else 5
+        dense_ms = timed(lambda: sd.attn_dense(q, k, v, out=out), reps)
+        sd.attn_dense(q, k, v, out=out, lse_out=lse)
+        select_ms = timed(lambda: sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, lse_in=lse, workspace=ws, index=index), reps)
+        select_own_ms = timed(lambda: sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, workspace=ws, index=index), reps)
+        sparse_ms = timed(lambda: sd.attn_sparse(q, k, v, index, out=out), 4 * reps)
+        f_dense, f_select, f_sparse = _flops(cfg, keep)
+        rec = {"config": {"B": cfg.B, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "L": cfg.L, "d": cfg.d, "block_q": cfg.bq, "block_k": cfg.bk,
+                          "rho": cfg.rho, "kept_blocks": keep},
+               "ms_per_call": {"dense": dense_ms, "select": select_ms, "select_with_own_statistics": select_own_ms, "sparse": sparse_ms},
+               "frac_of_peak": {"dense": f_dense / (dense_ms * 1e-3) / 1e12 / peak,
+                                "select_one_qkT": f_select / (select_ms * 1e-3) / 1e12 / peak,
+                                "sparse_executed": f_sparse / (sparse_ms * 1e-3) / 1e12 / peak}}
+        if cfg.T > 1:
+            layer = sd.SparseDLayer(cfg.T, 0.0, cfg.bq, cfg.bk, cfg.rho, n_dense=cfg.n_dense)
+            evs = []
+            for t in range(cfg.T):
+                qq, kk, vv = inp.rounded()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                layer.step(qq, kk, vv, t, out=out)
+                b.record()
+                evs.append((a, b))
+                inp.advance()
+            torch.cuda.synchronize()
+            total = sum(a.elapsed_time(b) for a, b in evs)
+            rec["schedule"] = {"T": cfg.T, "n_dense": cfg.n_dense, "total_attention_ms": total, "dense_only_ms": cfg.T * dense_ms,
+                               "speedup_measured": cfg.T * dense_ms / total,
+                               "expected_if_sparse_as_efficient_as_dense":
+                                   cfg.T / (cfg.n_dense + (cfg.T - cfg.n_dense) * keep / cfg.nkb + select_ms / dense_ms),
+                               "calls": layer.calls}
+        block[name] = rec
+        del inp, q, k, v, out, lse, ws, index
+        print(f"[bench] workload {name} done", file=sys.stderr, flush=True)
+    return block
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +230,8 @@ def main():
     ap.add_argument("--no-schedule", action="store_true", help="skip the full T-step schedule run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-clock", action="store_true", help="do not sample the shader clock under load")
+    ap.add_argument("--no-per-workload", action="store_true",
+                    help="skip the per-call times of the other named workloads (4k, 16k, 32k-GQA) appended to the headline line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE runs")
     args = ap.parse_args()
@@ -262,6 +343,7 @@ def main():
                           "calls": layer.calls})
             del inp2
 
+    traffic, traffic_info = _traffic_from_profiles(cfg.name)
     result = {
         "metric": "ms/layer-call + executed TFLOP/s (% bf16 MFMA peak) for sparse attn at 64k; schedule speedup",
         "value": sparse_tf,
@@ -284,7 +366,7 @@ def main():
         "pct_of_peak": {"dense": 100 * dense_tf / peak, "sparse_executed": 100 * sparse_tf / peak, "select_one_qkT": 100 * select_tf / peak},
         "schedule": sched,
         "roofline": {"kernel": "attn_sparse", "bound": "mfma", "achieved": sparse_tf, "peak": peak, "unit": "TFLOP/s",
-                     "frac": sparse_tf / peak, "traffic": _traffic_from_profiles(cfg.name)},
+                     "frac": sparse_tf / peak, "traffic": traffic, "traffic_provenance": traffic_info},
         "roofline_dense": {"kernel": "attn_dense", "bound": "mfma", "achieved": dense_tf, "peak": peak, "unit": "TFLOP/s",
                            "frac": dense_tf / peak},
         "roofline_select": {"kernel": "select_pattern (pooled scores + top-k, statistics reused)", "bound": "mfma",
@@ -306,6 +388,8 @@ def main():
         result["shader_clock_mhz"] = {"at_published_peak": 2400,
                                       "during_attn_dense": _sclk_while(lambda: sd.attn_dense(q, k, v, out=out)),
                                       "during_attn_sparse": _sclk_while(lambda: sd.attn_sparse(q, k, v, index, out=out))}
+    if not args.no_per_workload and cfg.name == "long64k":
+        result["per_workload"] = per_workload_block(sd, workload, torch, ("llada4k", "llada16k", "dream32k"), args.seed, peak)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, index, keep)
     print(json.dumps(result))
