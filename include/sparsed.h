@@ -118,9 +118,10 @@ typedef struct sparsed_exec {
  *    sample does not have are not written. nqb, nkb and cap_per_head are still those of L.
  *  - select_pattern_isolated: the same with two ranges per sample, [0, min(prefill_blocks, its blocks)) and
  *    the rest of its blocks, each with its own count; a sample no longer than the prefill has one range.
- *  - A length <= 0 makes the whole sample a no-op. A prefill boundary INSIDE a key block
- *    (select_pattern_isolated_tokens with prefill_tokens not a multiple of block_k) does not go with
- *    per-sample lengths (SPARSED_ERR_UNSUPPORTED).
+ *  - select_pattern_isolated_tokens: the same with the boundary at a key token p; a sample longer than p
+ *    splits the key block that holds p as described at that call (its generation part ends at the sample's
+ *    length), a sample no longer than p has one range over its own blocks.
+ *  - A length <= 0 makes the whole sample a no-op.
  */
 
 /*

@@ -278,9 +278,11 @@ def select_pattern_isolated(q, k, block_q: int, block_k: int, rho: float, prefil
 
 
 def select_pattern_isolated_tokens(q, k, block_q: int, block_k: int, rho: float, prefill_tokens: int, lse_in=None,
-                                   workspace=None, pooled_out=None, index: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
+                                   workspace=None, pooled_out=None, index: Optional[BlockIndex] = None, stream=None,
+                                   seq_lens: Optional[torch.Tensor] = None) -> BlockIndex:
     """sparsed_select_pattern_isolated_tokens: isolated selection with the boundary at a key token."""
-    return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, prefill_tokens=int(prefill_tokens))
+    return _select(q, k, block_q, block_k, rho, None, lse_in, workspace, pooled_out, index, stream, prefill_tokens=int(prefill_tokens),
+                   seq_lens=seq_lens)
 
 
 def attn_sparse(q, k, v, index: BlockIndex, out: Optional[torch.Tensor] = None, stream=None,

@@ -192,8 +192,6 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   if (ix->block_q != bq || ix->block_k != bk) return fail(SPARSED_ERR_INDEX, "block index blocks %dx%d differ from %dx%d", ix->block_q, ix->block_k, bq, bk);
   const int nqb = ix->nqb, nkb = ix->nkb;
   const int32_t* seq_lens = ex ? ex->seq_lens : nullptr;
-  if (seq_lens && boundary_token >= 0)
-    return fail(SPARSED_ERR_UNSUPPORTED, "a prefill boundary inside a key block does not go with per-sample lengths");
   if (nkb > 8192) return fail(SPARSED_ERR_UNSUPPORTED, "more than 8192 key blocks per row (%d)", nkb);
   int split = nkb, keep_lo, keep_hi = 0;
   const int straddle = boundary_token >= 0 ? boundary_token / bk : -1;  // the key block that holds the boundary
@@ -311,6 +309,7 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   t.L = q->L;
   t.rho = rho;
   t.straddle = straddle;
+  t.boundary = boundary_token;
   t.part = part;
   t.rows_tmp = rows_tmp;
   t.counts = counts;

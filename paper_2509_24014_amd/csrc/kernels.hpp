@@ -55,12 +55,13 @@ struct TopkArgs {
   // with score part[2r] (its prefill keys) and the second with part[2r+1] (its generation keys); it is
   // listed once even if both keep it, so rows differ in length: entries go to rows_tmp [rows, keep_lo +
   // keep_hi] and counts [rows], and compact_kernel builds the CSR from them.
-  // Per-sample lengths (optional, single range only): sample b ranks its first ceil(len/block_k) entries,
-  // keeps kept_blocks(rho, that many) of them, and its query blocks past ceil(len/block_q) get empty rows.
+  // Per-sample lengths (optional): sample b ranks the key blocks it has, ceil(len/block_k) of them, with its own
+  // counts kept_blocks(rho, size of each of its ranges), and its query blocks past ceil(len/block_q) get empty rows.
   const int32_t* seq_lens;
   int32_t heads_per_batch, block_q, block_k, L;
   double rho;
   int32_t straddle;
+  int32_t boundary;        // the boundary's key token (only with straddle >= 0)
   const float* part;
   int32_t* rows_tmp;
   int32_t* counts;

@@ -310,26 +310,55 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
   const int bh = r / a.nqb, I = r % a.nqb;
   const uint32_t* src = reinterpret_cast<const uint32_t*>(a.apool) + (int64_t)r * a.nkb;
   const int keep = a.keep_lo + a.keep_hi;
+  auto kept = [&](int nblocks) -> int {  // the host's count rule, in the same double arithmetic
+    if (nblocks <= 0) return 0;
+    double x = ceil(a.rho * (double)nblocks - 1e-9);
+    if (!(x >= 1.0)) x = 1.0;
+    if (x > (double)nblocks) x = (double)nblocks;
+    return (int)x;
+  };
   if (a.straddle >= 0) {
-    // The ranked row has nkb + 1 entries: blocks before the one that holds the boundary, that block's
-    // prefill part, its generation part, the blocks after it. `split` counts entries of this row.
-    const int Js = a.straddle, nv = a.nkb + 1;
+    // Prefill boundary at key token a.boundary, inside key block a.straddle. Rows differ in length, so they are
+    // staged at a fixed stride (the host's keep_lo + keep_hi) with their lengths; compact_kernel builds the CSR.
+    int L = a.L;  // length of this batch element
+    if (a.seq_lens != nullptr) {
+      const int len = a.seq_lens[bh / a.heads_per_batch];
+      L = len < a.L ? len : a.L;
+    }
+    const int nkb_b = L > 0 ? (L + a.block_k - 1) / a.block_k : 0, nqb_b = L > 0 ? (L + a.block_q - 1) / a.block_q : 0;
+    int32_t* tmp = a.rows_tmp + (int64_t)r * keep;
+    if (I >= nqb_b) {  // a query block this sample does not have: an empty row
+      if (lane == 0) a.counts[r] = 0;
+      return;
+    }
+    if (L <= a.boundary) {
+      // a sample no longer than the prefill: one range over the key blocks it has, none of them split
+      for (int J = lane; J < nkb_b; J += 64) row[J] = src[J];
+      __syncthreads();
+      const int keep_b = kept(nkb_b);
+      emit_topk_range(row, 0, nkb_b, keep_b, tmp, lane);
+      if (lane == 0) a.counts[r] = keep_b;
+      return;
+    }
+    // The ranked row has nkb_b + 1 entries: blocks before the one that holds the boundary, that block's
+    // prefill part, its generation part, the blocks after it. Entries [0, Js] are the prefill range.
+    const int Js = a.straddle, nv = nkb_b + 1;
+    const int keep_lo = kept(Js + 1), keep_hi = kept(nkb_b - Js), keep_b = keep_lo + keep_hi;
     const uint32_t* part = reinterpret_cast<const uint32_t*>(a.part) + (int64_t)r * 2;
     for (int v = lane; v < nv; v += 64) row[v] = v < Js ? src[v] : v == Js ? part[0] : v == Js + 1 ? part[1] : src[v - 1];
     __syncthreads();
     int32_t* sel = reinterpret_cast<int32_t*>(row + nv);  // the kept entries of both ranges, still in LDS
-    emit_topk_range(row, 0, a.split, a.keep_lo, sel, lane);
-    emit_topk_range(row, a.split, nv, a.keep_hi, sel + a.keep_lo, lane);
+    emit_topk_range(row, 0, Js + 1, keep_lo, sel, lane);
+    emit_topk_range(row, Js + 1, nv, keep_hi, sel + keep_lo, lane);
     __syncthreads();
     // entries -> key blocks; the only possible duplicate is the boundary block, at the junction of the two ranges
-    const bool dup = a.keep_lo > 0 && a.keep_hi > 0 && sel[a.keep_lo - 1] == Js && sel[a.keep_lo] == Js + 1;
-    int32_t* tmp = a.rows_tmp + (int64_t)r * keep;
-    for (int t = lane; t < keep; t += 64) {
-      if (dup && t == a.keep_lo) continue;
+    const bool dup = keep_lo > 0 && keep_hi > 0 && sel[keep_lo - 1] == Js && sel[keep_lo] == Js + 1;
+    for (int t = lane; t < keep_b; t += 64) {
+      if (dup && t == keep_lo) continue;
       const int v = sel[t];
-      tmp[t - ((dup && t > a.keep_lo) ? 1 : 0)] = v > Js ? v - 1 : v;
+      tmp[t - ((dup && t > keep_lo) ? 1 : 0)] = v > Js ? v - 1 : v;
     }
-    if (lane == 0) a.counts[r] = keep - (dup ? 1 : 0);
+    if (lane == 0) a.counts[r] = keep_b - (dup ? 1 : 0);
     return;
   }
   if (a.seq_lens != nullptr) {
@@ -337,13 +366,6 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
     const int len = a.seq_lens[bh / a.heads_per_batch];
     const int L = len < a.L ? len : a.L;
     const int nkb_b = L > 0 ? (L + a.block_k - 1) / a.block_k : 0, nqb_b = L > 0 ? (L + a.block_q - 1) / a.block_q : 0;
-    auto kept = [&](int nblocks) -> int {  // the host's count rule, in the same double arithmetic
-      if (nblocks <= 0) return 0;
-      double x = ceil(a.rho * (double)nblocks - 1e-9);
-      if (!(x >= 1.0)) x = 1.0;
-      if (x > (double)nblocks) x = (double)nblocks;
-      return (int)x;
-    };
     // With a prefill / generation split (Eq. 5) the sample's two ranges are [0, split) and [split, nkb_b), the
     // first cut to the blocks the sample has; a sample no longer than the prefill has one range only.
     const int split_b = a.split < nkb_b ? a.split : nkb_b;

@@ -97,8 +97,6 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_attn_sparse(R(q), R(k), R(v), None, R(o), None) == 1
     assert lib.sparsed_attn_sparse(R(q), R(k), R(v), R(_ix(H=4)), R(o), None) == 8
     assert lib.sparsed_select_pattern_isolated(R(q), R(k), 32, 32, 0.3, 9, R(_ix(cap=64)), None) == 5
-    exl = binding._Exec(None, None, 0, None, None, None, 0x5000)                           # per-sample lengths
-    assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=64)), R(exl)) == 6  # boundary inside a block + per-sample lengths
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 300, R(_ix(cap=64)), None) == 5   # boundary past L
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=8)), None) == 8    # capacity
     assert lib.sparsed_select_pattern_isolated_tokens(R(q), R(k), 32, 32, 0.3, 50, R(_ix(cap=64)), None) == 7   # workspace

@@ -581,6 +581,61 @@ def test_isolated_selection_with_per_sample_lengths(dtype, bq, bk, L, D, lens, p
         assert (out_s[b, :, n:] == 7.0).all()
 
 
+@pytest.mark.parametrize("dtype,bq,bk,L,D,lens,ptok,rho", [
+    # boundary inside key block 3; samples longer than it (two ranges, block 3 split), one ending inside block 3 after
+    # the boundary (a generation part of 10 keys), one ending before the boundary and one before block 3 (one range each)
+    (torch.bfloat16, 128, 64, 1024, 128, [1024, 700, 210, 199, 150, 64], 200, 0.3),
+    (torch.bfloat16, 64, 128, 1000, 64, [1000, 500, 301, 300, 257], 300, 0.4),        # 128-key blocks
+    (torch.bfloat16, 32, 32, 512, 128, [512, 100, 78, 77, 40], 77, 0.5),              # 32-key blocks
+    (torch.float32, 32, 32, 256, 64, [256, 100, 51, 50, 33, 20], 50, 0.3),
+])
+def test_isolated_selection_token_boundary_with_per_sample_lengths(dtype, bq, bk, L, D, lens, ptok, rho):
+    """A prefill boundary inside a key block in a padded batch (Eq. 5 on samples of different length): every sample
+    is ranked as if passed alone at its own length, with the boundary at min(p, its length)."""
+    B, H = len(lens), 2
+    _say(f"isolated selection, token boundary + per-sample lengths: {dtype} {bq}x{bk} L={L} p={ptok} lens={lens}")
+    q, k, v = _rand_qkv(B, H, H, L, D, dtype, seed=L + ptok + D, scale=1.0 if dtype == torch.float32 and D == 64 else 0.6)
+    qd, kd, vd = _dev(q, k, v)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    ix = sd.select_pattern_isolated_tokens(qd, kd, bq, bk, rho, ptok, seq_lens=sl)
+    sd.index_validate(ix)
+    out_s = torch.full((B, H, L, D), 7.0, dtype=dtype, device=DEV)
+    sd.attn_sparse(qd, kd, vd, ix, out=out_s, seq_lens=sl)
+    torch.cuda.synchronize()
+    rp, ci = ix.row_ptr.cpu().numpy(), ix.col_idx.cpu().numpy()
+    ties = short_rows = 0
+    for b, n in enumerate(lens):
+        qb, kb, vb = q[b:b + 1, :, :n], k[b:b + 1, :, :n], v[b:b + 1, :, :n]
+        nqb_b = -(-n // bq)
+        rp_o, ci_o, ap, n_pre, vblock = oracle.select_isolated_tokens(qb, kb, bq, bk, rho, min(ptok, n))
+        nv = ap.shape[-1]
+        keep_pre = oracle.kept_blocks(rho, n_pre)
+        keep_gen = oracle.kept_blocks(rho, nv - n_pre) if nv > n_pre else 0
+        for h in range(H):
+            assert rp[b, h, 0] == 0 and (rp[b, h, nqb_b:] == rp[b, h, nqb_b]).all()     # query blocks past the sample: empty rows
+            for I in range(nqb_b):
+                got = ci[b, h, rp[b, h, I]:rp[b, h, I + 1]].tolist()
+                want = ci_o[0, h, rp_o[0, h, I]:rp_o[0, h, I + 1]].tolist()
+                assert got == sorted(set(got)) and len(got) == len(want)
+                short_rows += (keep_gen > 0 and len(got) == keep_pre + keep_gen - 1)
+                if got == want:
+                    continue
+                a = ap[0, h, I]
+                cut_pre = np.sort(a[:n_pre])[::-1][keep_pre - 1]
+                cut_gen = np.sort(a[n_pre:])[::-1][keep_gen - 1] if keep_gen else 0.0
+                for J in set(got) ^ set(want):
+                    ok = any((abs(a[e] - (cut_pre if e < n_pre else cut_gen)) <= 1e-5 * (cut_pre if e < n_pre else cut_gen))
+                             for e in range(nv) if vblock[e] == J)
+                    assert ok, f"sample {b} head {h} row {I}: block {J} differs outside the tie band"
+                ties += 1
+        # sparse attention on the GPU-built rows of this sample, as if it had been passed alone
+        rp_b = rp[b:b + 1, :, :nqb_b + 1].copy()
+        want = oracle.attn_sparse(qb, kb, vb, rp_b, ci[b:b + 1], bq, bk)
+        assert_output_close(out_s[b:b + 1, :, :n], want, dtype, f"sparse sample {b}")
+        assert (out_s[b, :, n:] == 7.0).all()
+    _say(f"   rows_with_the_boundary_block_kept_twice={short_rows} tie_rows={ties}")
+
+
 # ----------------------------------------------------------------------------- seeded sweep over the parameter space
 def _sweep_cases(n, seed):
     rng = np.random.default_rng(seed)

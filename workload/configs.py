@@ -49,6 +49,10 @@ CONFIGS = {
     # Not one of the five named workloads: a short-running shape (same head dim, blocks and generator as
     # the long-context one) for hardware-counter runs, whose 32-bit counters saturate on longer kernels.
     "probe8k": WorkloadConfig("probe8k", 6, 1, 8, 8, 8192, 128, "bf16", 128, 64, 0.1, 1, 1, 0.0, True),
+    # Not one of the five named workloads: the long-context shape (same length, blocks and rho, so every work-group
+    # does exactly what it does there) cut to four heads, one of each planted type, so that one sparse-attention
+    # launch is short enough for hardware-counter runs.
+    "probe64k": WorkloadConfig("probe64k", 9, 1, 4, 4, 65536, 128, "bf16", 128, 64, 0.05, 1, 1, 0.0, True),
     # The paper's own long-context setting (Section 4.1: square blocks of 128, rho = 30 %, skip = 20 %) on the
     # long-context shape: not one of the five named workloads, used for one parity test and one line of measurements.
     "paper64k": WorkloadConfig("paper64k", 8, 1, 32, 32, 65536, 128, "bf16", 128, 128, 0.3, 1024, 205, 0.02, True),
