@@ -220,6 +220,46 @@ def per_workload_block(sd, workload, torch, names, seed, peak):
     return block
 
 
+def index_ablation(sd, torch, cfg, q, k, v, index, keep):
+    """The sparse kernel on the same tensors with other block indices of the same row length: separates what the
+    selected pattern's memory locality costs (against an index whose every K/V copy hits L2) from what a query
+    block costs beyond its tiles (rows of other lengths with the all-L2 index)."""
+    dev = q.device
+    out = torch.empty_like(q)
+    H, nqb, nkb = cfg.Hq, cfg.nqb, cfg.nkb
+
+    def timed(ix, rows_keep):
+        sd.attn_sparse(q, k, v, ix, out=out)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            sd.attn_sparse(q, k, v, ix, out=out)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 5
+        fl = 4.0 * cfg.B * H * nqb * rows_keep * cfg.bq * cfg.bk * cfg.d
+        return {"ms": ms, "tflops_executed": fl / (ms * 1e-3) / 1e12}
+
+    def regular(cols_of_row, kp):  # the same rows for every head
+        rp = (torch.arange(nqb + 1, dtype=torch.int32) * kp).repeat(cfg.B, H, 1).to(dev)
+        ci = cols_of_row.to(torch.int32).reshape(1, 1, nqb * kp).repeat(cfg.B, H, 1).contiguous().to(dev)
+        return sd.BlockIndex(rp, ci, cfg.bq, cfg.bk, nkb)
+
+    res = {"selected_pattern": timed(index, keep)}
+    first = torch.arange(keep).repeat(nqb, 1)
+    res["same_blocks_for_every_row_all_L2_hits"] = timed(regular(first, keep), keep)
+    g = torch.Generator().manual_seed(1)
+    rnd = torch.stack([torch.sort(torch.randperm(nkb, generator=g)[:keep])[0] for _ in range(nqb)])
+    res["uniform_random_blocks"] = timed(regular(rnd, keep), keep)
+    centre = (torch.arange(nqb) * cfg.bq // cfg.bk - keep // 2).clamp(min=0, max=nkb - keep)
+    res["diagonal_window"] = timed(regular(centre[:, None] + torch.arange(keep)[None, :], keep), keep)
+    res["row_length_sweep_all_L2_hits"] = {}
+    for kp in (keep // 4, keep // 2, keep, 2 * keep, 4 * keep):
+        if 1 <= kp <= nkb:
+            res["row_length_sweep_all_L2_hits"][str(kp)] = timed(regular(torch.arange(kp).repeat(nqb, 1), kp), kp)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +272,8 @@ def main():
     ap.add_argument("--no-clock", action="store_true", help="do not sample the shader clock under load")
     ap.add_argument("--no-per-workload", action="store_true",
                     help="skip the per-call times of the other named workloads (4k, 16k, 32k-GQA) appended to the headline line")
+    ap.add_argument("--index-ablation", action="store_true",
+                    help="also time the sparse kernel on other block indices of the same row length (all-L2, random, window)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE runs")
     args = ap.parse_args()
@@ -388,6 +430,8 @@ def main():
         result["shader_clock_mhz"] = {"at_published_peak": 2400,
                                       "during_attn_dense": _sclk_while(lambda: sd.attn_dense(q, k, v, out=out)),
                                       "during_attn_sparse": _sclk_while(lambda: sd.attn_sparse(q, k, v, index, out=out))}
+    if args.index_ablation:
+        result["index_ablation"] = index_ablation(sd, torch, cfg, q, k, v, index, keep)
     if not args.no_per_workload and cfg.name == "long64k":
         result["per_workload"] = per_workload_block(sd, workload, torch, ("llada4k", "llada16k", "dream32k"), args.seed, peak)
     if not args.no_cpu_baseline:
