@@ -26,7 +26,8 @@ namespace sparsed {
 // KB: keys per listed block in sparse mode (64 or 128), a compile-time choice.
 template <int D, int NQ, int NW, Mode MODE, int KB = kTileK>
 __global__ __launch_bounds__(NW * 64)
-    __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? 2 : 1, (NQ == 1 && NW >= 4) ? 2 : 1))) void attn_bf16_kernel(const AttnArgs a) {
+    __attribute__((amdgpu_waves_per_eu((NQ == 1 && NW >= 4) ? (MODE == Mode::kStats ? 4 : 2) : 1,
+                                       (NQ == 1 && NW >= 4) ? (MODE == Mode::kStats ? 4 : 2) : 1))) void attn_bf16_kernel(const AttnArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64;
   constexpr int QT = 32 * NQ * NW;
@@ -337,12 +338,17 @@ __global__ __launch_bounds__(NW * 64)
   // slot c of row r at position c ^ (r mod slots) so that neither side has bank conflicts beyond 2-way.
   constexpr int kRowBytes = 2 * D, kSlots = D / 8, kRowsPerStore = 64 / kSlots;
   static_assert(32 * kRowBytes * 2 <= kKBytes && (!kHasV || 32 * kRowBytes * 2 <= kVBytes), "two waves share one buffer");
+  // (The lane-derived values of this part are worked out afresh from an opaque copy of the lane number, so that
+  // none of them is kept in a register, or spilled, across the tile loop.)
+  int lane_e = lane;
+  asm volatile("" : "+v"(lane_e));
+  const int je = lane_e & 31, ge = lane_e >> 5;
   char* const stage = ((wave >> 1) == 0 ? kbuf0 : (wave >> 1) == 1 ? kbuf1 : (wave >> 1) == 2 ? vbuf0 : vbuf1) + (wave & 1) * (32 * kRowBytes);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const float ltot = pair_sum(lsum[nq]);
-    const int row = row0 + nq * 32 + j;
-    if (a.lse != nullptr && g == 0 && row < L)
+    const int row = row0 + nq * 32 + je;
+    if (a.lse != nullptr && ge == 0 && row < L)
       a.lse[(int64_t)bh * a.L + row] = (M[nq] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
     if (kHasV) {
       const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
@@ -356,12 +362,12 @@ __global__ __launch_bounds__(NW * 64)
           w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
           w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
           // columns 32*dt + 8*q4 + 4*g .. +3 of row j: slot 4*dt + q4, half g
-          *reinterpret_cast<u32x2*>(stage + j * kRowBytes + (((4 * dt + q4) ^ (j & (kSlots - 1))) << 4) + 8 * g) = w;
+          *reinterpret_cast<u32x2*>(stage + je * kRowBytes + (((4 * dt + q4) ^ (je & (kSlots - 1))) << 4) + 8 * ge) = w;
         }
       __bf16* const obase = static_cast<__bf16*>(a.o) + b * a.o_sb + h * a.o_sh;
 #pragma unroll
       for (int it = 0; it < 32 / kRowsPerStore; ++it) {
-        const int r = it * kRowsPerStore + lane / kSlots, slot = lane % kSlots;
+        const int r = it * kRowsPerStore + lane_e / kSlots, slot = lane_e % kSlots;
         const u32x4 w = *reinterpret_cast<const u32x4*>(stage + r * kRowBytes + ((slot ^ (r & (kSlots - 1))) << 4));
         const int grow = row0 + nq * 32 + r;
         if (grow < L) *reinterpret_cast<u32x4*>(obase + (int64_t)grow * a.o_sl + slot * 8) = w;  // partial last query tile: rows past L are dropped

@@ -32,7 +32,7 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float x) {
 // per-lane sums are reduced over the wave, then over the waves through LDS in a fixed order.
 // HALF: key blocks of 32 (the two 32-key sub-tiles of a tile are pooled separately).
 template <int D, int NW, bool HALF>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 2 ? 2 : 1, NW >= 2 ? 2 : 1)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 4 : NW >= 2 ? 2 : 1, NW >= 4 ? 4 : NW >= 2 ? 2 : 1)))
 void pool_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64;
