@@ -147,7 +147,8 @@ sparsed_status sparsed_attn_dense(const sparsed_tensor* q, const sparsed_tensor*
  * (every row has exactly k entries, row_ptr[I] = I*k); its B, H, nqb, nkb,
  * block_q, block_k must already describe q and the blocks and cap_per_head must
  * be >= nqb*k, else SPARSED_ERR_INDEX. Needs ex->workspace of at least
- * sparsed_select_workspace_bytes() bytes (SPARSED_ERR_WORKSPACE otherwise); the
+ * sparsed_select_workspace_min_bytes() bytes (SPARSED_ERR_WORKSPACE otherwise;
+ * sparsed_select_workspace_bytes() lets it pool in one pass over the keys); the
  * workspace holds the row statistics and the pooled scores while the call's
  * kernels run, so calls that may overlap on the GPU need a workspace each.
  */
@@ -164,8 +165,8 @@ sparsed_status sparsed_select_pattern(const sparsed_tensor* q, const sparsed_ten
  * the library runs on holds its own copy until the process ends. ex->workspace is ignored;
  * ex->stream, lse_in, pooled_out and seq_lens work as in sparsed_select_pattern. The call
  * allocates and frees nothing (its first call on a device looks the array's device address up
- * once). Returns SPARSED_ERR_WORKSPACE when sparsed_select_workspace_bytes() for these arguments
- * exceeds SPARSED_STATIC_SCRATCH_BYTES (e.g. 32 heads of 65536 tokens with 128 x 64 blocks need
+ * once). Returns SPARSED_ERR_WORKSPACE when sparsed_select_workspace_min_bytes() for these arguments
+ * (the _min_ form) exceeds SPARSED_STATIC_SCRATCH_BYTES (e.g. 32 heads of 65536 tokens with 128 x 64 blocks need
  * 75 MB; 32 heads of 16384 tokens with 64 x 64 blocks need 10 MB and fit). All calls on one GPU
  * share that GPU's array, which keeps the previous call's contents (every entry a call reads it
  * has written first): calls that may overlap on one GPU race, so keep them on one stream or
@@ -251,8 +252,17 @@ int32_t sparsed_kept_blocks(double rho, int32_t n);
  */
 int32_t sparsed_n_dense_steps(int32_t T, double skip);
 
-/* Bytes of workspace sparsed_select_pattern needs for this q and these blocks (0 on bad arguments). */
+/*
+ * Bytes of workspace the selection calls want for this q and these blocks (0 on bad arguments): the row statistics,
+ * the pooled scores and, for bf16 inputs, the slabs of the one-pass pooled-score kernel that is used when no
+ * ex->lse_in is handed over (block_q x nkb floats for each of a few hundred resident work-groups: 400 MB for 32
+ * heads of 65536 tokens in 128 x 64 blocks). sparsed_select_workspace_min_bytes() is the part every call needs
+ * (statistics + pooled scores, 75 MB in that example); with a workspace between the two, or with ex->lse_in set,
+ * selection runs as row statistics (unless handed over) followed by pooled scores, two passes over the keys, with
+ * the same results up to fp32 summation order.
+ */
 size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);
+size_t sparsed_select_workspace_min_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);
 
 /* The same for sparsed_select_pattern_isolated_tokens (a little more: two extra pooled columns and row staging). */
 size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k);

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     select_pattern_static,
     STATIC_SCRATCH_BYTES,
     select_workspace_bytes,
+    select_workspace_min_bytes,
     version,
 )
 from .schedule import SparseDLayer  # noqa: F401

@@ -25,7 +25,7 @@ EXPORTS = [
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
     "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16",
     "sparsed_select_pattern_isolated_tokens", "sparsed_select_tokens_workspace_bytes",
-    "sparsed_select_pattern_static",
+    "sparsed_select_pattern_static", "sparsed_select_workspace_min_bytes",
 ]
 
 
@@ -89,6 +89,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_n_dense_steps.restype = ctypes.c_int32
     lib.sparsed_select_workspace_bytes.argtypes = [T, ctypes.c_int32, ctypes.c_int32]
     lib.sparsed_select_workspace_bytes.restype = ctypes.c_size_t
+    lib.sparsed_select_workspace_min_bytes.argtypes = [T, ctypes.c_int32, ctypes.c_int32]
+    lib.sparsed_select_workspace_min_bytes.restype = ctypes.c_size_t
     lib.sparsed_index_validate.argtypes = [I, E]
     lib.sparsed_index_validate.restype = ctypes.c_int
     lib.sparsed_index_fill_window.argtypes = [I, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, E]
@@ -174,9 +176,17 @@ def n_dense_steps(T: int, skip: float) -> int:
 
 
 def select_workspace_bytes(q: torch.Tensor, block_q: int, block_k: int) -> int:
+    """sparsed_select_workspace_bytes: the workspace that lets selection pool in one pass when no lse is handed over."""
     B, H, L, D = q.shape
     t = _Tensor(None, SPARSED_BF16 if q.dtype == torch.bfloat16 else SPARSED_F32, B, H, L, D, 0, 0, 0)
     return int(load_library().sparsed_select_workspace_bytes(ctypes.byref(t), block_q, block_k))
+
+
+def select_workspace_min_bytes(q: torch.Tensor, block_q: int, block_k: int) -> int:
+    """sparsed_select_workspace_min_bytes: the least the selection calls accept (statistics + pooled scores)."""
+    B, H, L, D = q.shape
+    t = _Tensor(None, SPARSED_BF16 if q.dtype == torch.bfloat16 else SPARSED_F32, B, H, L, D, 0, 0, 0)
+    return int(load_library().sparsed_select_workspace_min_bytes(ctypes.byref(t), block_q, block_k))
 
 
 def _seq_lens_ptr(seq_lens, B):
@@ -219,8 +229,12 @@ def _select(q, k, block_q, block_k, rho, prefill_blocks, lse_in, workspace, pool
                            torch.empty(B, H, max(nqb * keep, 1), dtype=torch.int32, device=q.device), block_q, block_k, nkb)
     if workspace is None:
         tq0 = _tensor(q, "q")
-        need = (select_workspace_bytes(q, block_q, block_k) if prefill_tokens is None
-                else int(lib.sparsed_select_tokens_workspace_bytes(ctypes.byref(tq0), block_q, block_k)))
+        if prefill_tokens is not None:
+            need = int(lib.sparsed_select_tokens_workspace_bytes(ctypes.byref(tq0), block_q, block_k))
+        elif lse_in is not None:
+            need = select_workspace_min_bytes(q, block_q, block_k)   # the slabs of the one-pass kernel would go unused
+        else:
+            need = select_workspace_bytes(q, block_q, block_k)
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     if pooled_out is not None and (pooled_out.dtype != torch.float32 or not pooled_out.is_contiguous()
                                    or pooled_out.numel() != B * H * nqb * nkb):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparsed.so")
-SOURCES = ["api.hip", "attn_bf16.hip", "attn_bf16_splitk.hip", "attn_f32.hip", "select.hip", "probe.hip"]
+SOURCES = ["api.hip", "attn_bf16.hip", "attn_bf16_splitk.hip", "attn_f32.hip", "select.hip", "select_onepass.hip", "probe.hip"]
 HEADERS = ["kernels.hpp", "tile_bf16.hpp", "tile_f32.hpp", os.path.join("..", "..", "include", "sparsed.h"),
            os.path.join("..", "..", "include", "sparsed_diag.h")]
 # packed fp32 VALU forms are disabled on purpose: some of their encodings have given silently wrong results on this chip

@@ -133,6 +133,12 @@ size_t select_ws_bytes(int B, int Hq, int L, int nqb, int nkb) {
   return align256((size_t)B * Hq * L * sizeof(float)) + align256((size_t)B * Hq * nqb * nkb * sizeof(float));
 }
 
+// Scratch of the one-pass pooled-score kernel (bf16 inputs without a handed-over log-sum-exp): one slab of
+// block_q x (key blocks rounded up to 16) floats per persistent work-group.
+int onepass_slab_ld(int nkb) { return (nkb + 15) & ~15; }
+size_t onepass_slab_bytes(int bq, int nkb) { return align256((size_t)bq * onepass_slab_ld(nkb) * sizeof(float)); }
+constexpr int kOnepassMinGroups = 256;  // fewer slabs than compute units (and than pooled rows): the two-pass form is used instead
+
 // Extra scratch when the prefill boundary falls inside a key block: the two partial scores of that
 // block per pooled row, fixed-stride rows of kept blocks (at most nkb + 1 each) and their lengths.
 size_t select_tokens_extra_bytes(int B, int Hq, int nqb, int nkb) {
@@ -230,28 +236,10 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   hipStream_t s = stream_of(ex);
   const bool bf16 = q->dtype == SPARSED_BF16;
 
-  // 1. row log-sum-exp of Eq. 1's logits, unless the caller passes the one attn_dense produced
   const float* lse = ex ? ex->lse_in : nullptr;
-  if (!lse) {
-    AttnArgs a{};
-    a.q = targ(q);
-    a.k = targ(k);
-    a.lse = lse_buf;
-    a.B = q->B;
-    a.Hq = q->H;
-    a.Hkv = k->H;
-    a.L = q->L;
-    a.seq_lens = seq_lens;
-    a.scale_log2 = scale_log2(q->D);
-    const hipError_t e = bf16 ? launch_attn_bf16(Mode::kStats, q->D, 0, a, s) : launch_attn_f32(Mode::kStats, q->D, 0, a, s);
-    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
-    lse = lse_buf;
-  }
-  // 2. pooled scores A'
   PoolArgs p{};
   p.q = targ(q);
   p.k = targ(k);
-  p.lse = lse;
   p.apool = apool;
   p.B = q->B;
   p.Hq = q->H;
@@ -265,8 +253,48 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   p.out_stride = nkb;
   p.out_col0 = 0;
   p.scale_log2 = scale_log2(q->D);
-  hipError_t e = bf16 ? launch_pool_bf16(q->D, bq, p, s) : launch_pool_f32(q->D, bq, p, s);
-  if (e != hipSuccess) return hip_fail(e, "pooled-score launch");
+  hipError_t e = hipSuccess;
+  const size_t rows_total = (size_t)q->B * q->H * nqb;  // pooled rows = (head, query block) units
+  // How many one-pass slabs the scratch behind `need` has room for.
+  const size_t ws_bytes = fixed_scratch ? fixed_scratch_bytes : ex->workspace_bytes;
+  const size_t slab_bytes = onepass_slab_bytes(bq, nkb);
+  size_t slabs = (ws_bytes - need) / slab_bytes;
+  if (slabs > (size_t)pool1p_groups(bq)) slabs = (size_t)pool1p_groups(bq);
+  if (slabs > rows_total) slabs = rows_total;
+  const size_t slabs_needed = rows_total < (size_t)kOnepassMinGroups ? rows_total : (size_t)kOnepassMinGroups;
+  if (!lse && bf16 && slabs >= slabs_needed) {
+    // 1 + 2. no log-sum-exp handed over: pooled scores A' (and the row log-sum-exp) in one pass over the keys
+    p.slab = reinterpret_cast<float*>(ws + need);
+    p.slab_ld = onepass_slab_ld(nkb);
+    p.lse_out = lse_buf;
+    e = launch_pool1p_bf16(q->D, bq, p, (int)slabs, s);
+    if (e != hipSuccess) return hip_fail(e, "one-pass pooled-score launch");
+    lse = lse_buf;
+    p.slab = nullptr;
+    p.lse_out = nullptr;
+  } else {
+    // 1. row log-sum-exp of Eq. 1's logits, unless the caller passes the one attn_dense produced
+    if (!lse) {
+      AttnArgs a{};
+      a.q = targ(q);
+      a.k = targ(k);
+      a.lse = lse_buf;
+      a.B = q->B;
+      a.Hq = q->H;
+      a.Hkv = k->H;
+      a.L = q->L;
+      a.seq_lens = seq_lens;
+      a.scale_log2 = scale_log2(q->D);
+      e = bf16 ? launch_attn_bf16(Mode::kStats, q->D, 0, a, s) : launch_attn_f32(Mode::kStats, q->D, 0, a, s);
+      if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+      lse = lse_buf;
+    }
+    // 2. pooled scores A'
+    p.lse = lse;
+    e = bf16 ? launch_pool_bf16(q->D, bq, p, s) : launch_pool_f32(q->D, bq, p, s);
+    if (e != hipSuccess) return hip_fail(e, "pooled-score launch");
+  }
+  p.lse = lse;
   const size_t rows = (size_t)q->B * q->H * nqb;
   float* part = nullptr;
   int32_t *rows_tmp = nullptr, *counts = nullptr;
@@ -369,10 +397,21 @@ sparsed_status sparsed_select_pattern_isolated_tokens(const sparsed_tensor* q, c
   return select_impl(q, k, block_q, block_k, rho, 0, true, out_block_index, ex, prefill_tokens);
 }
 
+// slabs of the one-pass kernel, if these inputs can use it
+size_t onepass_bytes(const sparsed_tensor* q, int32_t block_q, int32_t nkb) {
+  if (q->dtype != SPARSED_BF16 || (block_q != 32 && block_q != 64 && block_q != 128)) return 0;
+  return (size_t)pool1p_groups(block_q) * onepass_slab_bytes(block_q, nkb);
+}
+
 size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
   if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
   const int nqb = ceil_div(q->L, block_q), nkb = ceil_div(q->L, block_k);
-  return select_ws_bytes(q->B, q->H, q->L, nqb, nkb) + select_tokens_extra_bytes(q->B, q->H, nqb, nkb);
+  return select_ws_bytes(q->B, q->H, q->L, nqb, nkb) + select_tokens_extra_bytes(q->B, q->H, nqb, nkb) + onepass_bytes(q, block_q, nkb);
+}
+
+size_t sparsed_select_workspace_min_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
+  if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
+  return select_ws_bytes(q->B, q->H, q->L, ceil_div(q->L, block_q), ceil_div(q->L, block_k));
 }
 
 int32_t sparsed_kept_blocks(double rho, int32_t n) {
@@ -393,7 +432,8 @@ int32_t sparsed_n_dense_steps(int32_t T, double skip) {
 
 size_t sparsed_select_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {
   if (!q || block_q <= 0 || block_k <= 0 || q->B <= 0 || q->H <= 0 || q->L <= 0) return 0;
-  return select_ws_bytes(q->B, q->H, q->L, ceil_div(q->L, block_q), ceil_div(q->L, block_k));
+  return select_ws_bytes(q->B, q->H, q->L, ceil_div(q->L, block_q), ceil_div(q->L, block_k)) +
+         onepass_bytes(q, block_q, ceil_div(q->L, block_k));
 }
 
 sparsed_status sparsed_index_validate(const sparsed_block_index* ix, const sparsed_exec* ex) {

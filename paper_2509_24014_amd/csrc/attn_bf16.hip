@@ -44,7 +44,7 @@ __global__ __launch_bounds__(NW * 64)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
-  const int j = lane & 31, g = lane >> 5;
+  const int g = lane >> 5;
 
   const int lid = xcd_remap(blockIdx.x, gridDim.x);
   const int qt = lid % a.n_qtiles;

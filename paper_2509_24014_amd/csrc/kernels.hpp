@@ -40,6 +40,10 @@ struct PoolArgs {
   int32_t key_begin, key_len;
   int32_t out_stride, out_col0;
   float scale_log2;        // log2(e) / sqrt(D)
+  // one-pass form only (pool1p_bf16_kernel; whole key range, lse unused):
+  float* slab;             // scratch, one slab of block_q x slab_ld floats per work-group of the launch
+  int32_t slab_ld;         // floats per slab row: the key-block count rounded up to a multiple of 16
+  float* lse_out;          // optional [B, Hq, L]: receives the row log-sum-exp
 };
 
 // Arguments of the per-row top-k kernel (Eq. 6): one wavefront per pooled row.
@@ -102,6 +106,10 @@ hipError_t launch_attn_f32(Mode mode, int D, int block_q, AttnArgs a, hipStream_
 hipError_t launch_attn_bf16_splitk(int D, int block_q, const AttnArgs& a, hipStream_t s);
 hipError_t launch_pool_bf16(int D, int block_q, const PoolArgs& a, hipStream_t s);
 hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s);
+// Pooled scores of bf16 inputs in one pass over the keys (no row statistics needed): `groups` persistent work-groups,
+// each with its own slab in a.slab. pool1p_groups: the number of work-groups that fills the chip for this block_q.
+hipError_t launch_pool1p_bf16(int D, int block_q, const PoolArgs& a, int groups, hipStream_t s);
+int pool1p_groups(int block_q);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t s);
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);

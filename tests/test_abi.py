@@ -112,11 +112,17 @@ def test_argument_validation_rejects_before_any_launch():
 
 def test_workspace_size_formula():
     lib = binding.load_library()
+    lib.sparsed_select_workspace_min_bytes.argtypes = lib.sparsed_select_workspace_bytes.argtypes
+    lib.sparsed_select_workspace_min_bytes.restype = ctypes.c_size_t
     t = _t(B=1, H=32, L=65536, D=128, dtype=binding.SPARSED_BF16)
-    need = lib.sparsed_select_workspace_bytes(ctypes.byref(t), 128, 64)
-    assert need == 32 * 65536 * 4 + 32 * 512 * 1024 * 4
-    r = _t(B=1, H=2, L=250, D=64)
+    least = lib.sparsed_select_workspace_min_bytes(ctypes.byref(t), 128, 64)
+    assert least == 32 * 65536 * 4 + 32 * 512 * 1024 * 4                                # row statistics + pooled scores
+    full = lib.sparsed_select_workspace_bytes(ctypes.byref(t), 128, 64)
+    slab = 128 * 1024 * 4                                                               # block_q x nkb floats per resident work-group
+    assert full > least and (full - least) % slab == 0 and 256 <= (full - least) // slab <= 1024
+    r = _t(B=1, H=2, L=250, D=64)                                                       # fp32: two passes only
     assert lib.sparsed_select_workspace_bytes(ctypes.byref(r), 32, 32) == 2048 + 2 * 8 * 8 * 4   # ceil(250/32) = 8 blocks each way
+    assert lib.sparsed_select_workspace_min_bytes(ctypes.byref(r), 32, 32) == 2048 + 2 * 8 * 8 * 4
     assert lib.sparsed_select_workspace_bytes(ctypes.byref(t), 0, 64) == 0
 
 

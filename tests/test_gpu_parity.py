@@ -179,6 +179,17 @@ def _check_selection(q, k, bq, bk, rho, use_lse, what):
     assert rel.max() < 5e-6, f"{what}: pooled scores off by {rel.max():.2e} relative"
     tie_rows, tie_blocks = compare_index(ix.col_idx.cpu().numpy()[..., :nqb * keep], col_idx, apool.reshape(-1, nkb), keep)
     _say(f"{what}: rows={B * Hq * nqb} keep={keep} tie_rows={tie_rows} tie_blocks={tie_blocks} pooled_rel_err={rel.max():.2e}")
+    if not use_lse and q.dtype == torch.bfloat16:
+        # with the full workspace the call above pooled in one pass over the keys; with the least workspace the same
+        # call runs row statistics and pooled scores as two passes: both must meet the same bar
+        pooled2 = torch.empty_like(pooled)
+        ws_min = torch.empty(sd.select_workspace_min_bytes(qd, bq, bk), dtype=torch.uint8, device=DEV)
+        ix2 = sd.select_pattern(qd, kd, bq, bk, rho, workspace=ws_min, pooled_out=pooled2)
+        rel2 = np.abs(pooled2.cpu().double().numpy() - apool) / apool
+        assert rel2.max() < 5e-6, f"{what}: two-pass pooled scores off by {rel2.max():.2e} relative"
+        compare_index(ix2.col_idx.cpu().numpy()[..., :nqb * keep], col_idx, apool.reshape(-1, nkb), keep)
+        assert not torch.equal(pooled2, pooled) or rel.max() == 0     # two different kernels ran
+        _say(f"{what}: two-pass route pooled_rel_err={rel2.max():.2e}")
     return ix
 
 
@@ -194,6 +205,55 @@ def test_select_bf16(bq, L, Hq, Hkv, D, rho, use_lse):
 def test_select_f32(bq, bk, L, D, use_lse):
     q, k, _ = _rand_qkv(1, 2, 2, L, D, torch.float32, seed=bq + bk, scale=1.0 if D == 64 else 0.45)
     _check_selection(q, k, bq, bk, 0.3, use_lse, f"select f32 {bq}x{bk} L={L}")
+
+
+@pytest.mark.parametrize("bq,bk,L,D", [(128, 64, 1024, 128), (64, 32, 600, 64), (32, 128, 1000, 128)])
+def test_select_one_pass_re_references_rows_whose_logits_climb(bq, bk, L, D):
+    """The one-pass pooled-score kernel takes each row's reference from its first 32 keys. Here the logits climb by
+    hundreds of octaves along the keys (every row's mass ends up in its last blocks), so the reference has to be
+    raised again and again and everything a row has parked so far rescaled. Row log-sum-exp and pooled scores
+    must still match the oracle wherever the oracle's value is representable in fp32."""
+    H = 2
+    g = torch.Generator().manual_seed(L + D)
+    q = torch.zeros(1, H, L, D)
+    k = torch.zeros(1, H, L, D)
+    q[..., 0] = 8.0 + torch.rand(1, H, L, generator=g)                      # q . k / sqrt(D) = q0 * k0 / sqrt(D)
+    ramp = torch.linspace(0.0, 1.0, L) ** 2                                 # slow at first, then steep
+    k[..., 0] = (ramp * 40.0 * math.sqrt(D))[None, None, :] * (1.0 + 0.25 * torch.rand(1, H, L, generator=g))
+    q[..., 1:] = 0.05 * torch.randn(1, H, L, D - 1, generator=g)
+    k[..., 1:] = 0.05 * torch.randn(1, H, L, D - 1, generator=g)
+    q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
+    logit_span = float((q[..., 0].float().max() * k[..., 0].float().max()) / math.sqrt(D))
+    assert logit_span > 300                                                  # > 430 octaves from first to last key
+    qd, kd = _dev(q, k)
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    pooled = torch.empty(1, H, nqb, nkb, dtype=torch.float32, device=DEV)
+    ix = sd.select_pattern(qd, kd, bq, bk, 0.25, pooled_out=pooled)
+    sd.index_validate(ix)
+    row_ptr, col_idx, apool, _ = oracle.select_pattern(q, k, bq, bk, 0.25)
+    got = pooled.cpu().double().numpy()
+    big = apool > 1e-30                                                      # what fp32 can hold with full precision
+    assert big.any() and (~big).any()
+    rel = np.abs(got[big] - apool[big]) / apool[big]
+    # fp32 logits of this size carry an error of |logit| * 2^-24 octaves, i.e. a relative error of that times ln 2 in
+    # the exponential: the bar here scales with the span (the ordinary bar of 5e-6 holds for ordinary logits)
+    tol = 5e-6 + 2e-7 * logit_span * 1.4427
+    assert rel.max() < tol, f"pooled scores off by {rel.max():.2e} relative (bar {tol:.1e})"
+    assert (got[~big] <= 1e-29).all()
+    # the two-pass route on the same input, the same bar
+    pooled2 = torch.empty_like(pooled)
+    ws_min = torch.empty(sd.select_workspace_min_bytes(qd, bq, bk), dtype=torch.uint8, device=DEV)
+    sd.select_pattern(qd, kd, bq, bk, 0.25, workspace=ws_min, pooled_out=pooled2)
+    got2 = pooled2.cpu().double().numpy()
+    assert (np.abs(got2[big] - apool[big]) / apool[big]).max() < tol
+    keep = oracle.kept_blocks(0.25, nkb)
+    # the kept sets agree wherever the cut is at a representable score
+    cut = np.sort(apool.reshape(-1, nkb), axis=1)[:, ::-1][:, keep - 1]
+    rows_ok = cut > 1e-30
+    g_rows = ix.col_idx.cpu().numpy().reshape(-1, keep)[rows_ok]
+    o_rows = col_idx.reshape(-1, keep)[rows_ok]
+    compare_index(g_rows, o_rows, apool.reshape(-1, nkb)[rows_ok], keep)
+    _say(f"re-reference {bq}x{bk} L={L}: logit span {logit_span:.0f}, pooled rel err {rel.max():.2e}, rows checked {int(rows_ok.sum())}")
 
 
 def test_select_ties_resolve_to_lower_block_index():
@@ -954,7 +1014,9 @@ def _check_workload_sampled(name, n_per_type, check_dense=True):
     dense = sd.attn_dense(q, k, v, lse_out=lse)
     pooled = torch.empty(cfg.B, cfg.Hq, cfg.nqb, cfg.nkb, dtype=torch.float32, device=DEV)
     ix = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, lse_in=lse, pooled_out=pooled)
-    ix2 = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho)           # own statistics pass
+    pooled_own = torch.empty_like(pooled)
+    ix2 = sd.select_pattern(q, k, cfg.bq, cfg.bk, cfg.rho, pooled_out=pooled_own)   # nothing handed over: one pass over the keys
+    cols_own = ix2.col_idx.view(cfg.B, cfg.Hq, cfg.nqb, keep)
     sd.index_validate(ix)
     sparse = sd.attn_sparse(q, k, v, ix)
     torch.cuda.synchronize()
@@ -969,7 +1031,7 @@ def _check_workload_sampled(name, n_per_type, check_dense=True):
     # sampled units against the oracle
     group = cfg.Hq // cfg.Hkv
     tie_rows = tie_blocks = 0
-    pooled_err = dense_err = sparse_err = 0.0
+    pooled_err = pooled_own_err = dense_err = sparse_err = 0.0
     units = _sample_units(cfg, n_per_type, seed=1)
     assert len(units) >= 64
     cache = {}
@@ -992,6 +1054,11 @@ def _check_workload_sampled(name, n_per_type, check_dense=True):
         # the gate sits below the 1e-5 tie band of the ranking (Eq. 6) that these scores feed
         assert rel.max() <= 5e-6, f"{name} pooled h={h} I={I}: {rel.max():.2e}"
         pooled_err = max(pooled_err, float(rel.max()))
+        # the same unit from the call that was handed no row statistics
+        rel_own = np.abs(pooled_own[0, h, I].cpu().double().numpy() - ap[0]) / ap[0]
+        assert rel_own.max() <= 5e-6, f"{name} pooled (one pass) h={h} I={I}: {rel_own.max():.2e}"
+        pooled_own_err = max(pooled_own_err, float(rel_own.max()))
+        compare_index(cols_own[0, h, I].cpu().numpy(), ci.reshape(-1), ap.reshape(1, cfg.nkb), keep)
         # sparse output against the oracle run on the GPU-selected row
         rp1 = np.zeros((1, 1, cfg.nqb + 1), dtype=np.int32)
         rp1[0, 0, I + 1:] = keep
@@ -999,7 +1066,7 @@ def _check_workload_sampled(name, n_per_type, check_dense=True):
         want = oracle.attn_sparse_rows(qh, kh, vh, rp1, ci1, cfg.bq, cfg.bk, 0, 0, I, I + 1)
         sparse_err = max(sparse_err, assert_output_close(sparse[0, h, r0:r1], want, torch.bfloat16, f"{name} sparse h={h} I={I}")[0])
     _say(f"{name}: {len(units)} units checked; tie_rows={tie_rows} tie_blocks={tie_blocks} "
-         f"max pooled rel err={pooled_err:.2e} dense max|d|={dense_err:.2e} sparse max|d|={sparse_err:.2e}")
+         f"max pooled rel err={pooled_err:.2e} (one pass: {pooled_own_err:.2e}) dense max|d|={dense_err:.2e} sparse max|d|={sparse_err:.2e}")
 
 
 def test_workload_llada4k_full_tensor():
