@@ -197,23 +197,33 @@ def per_workload_block(sd, workload, torch, names, seed, peak):
                                 "select_one_qkT": f_select / (select_ms * 1e-3) / 1e12 / peak,
                                 "sparse_executed": f_sparse / (sparse_ms * 1e-3) / 1e12 / peak}}
         if cfg.T > 1:
-            layer = sd.SparseDLayer(cfg.T, 0.0, cfg.bq, cfg.bk, cfg.rho, n_dense=cfg.n_dense)
-            evs = []
-            for t in range(cfg.T):
-                qq, kk, vv = inp.rounded()
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                layer.step(qq, kk, vv, t, out=out)
-                b.record()
-                evs.append((a, b))
-                inp.advance()
-            torch.cuda.synchronize()
-            total = sum(a.elapsed_time(b) for a, b in evs)
+            def run_schedule(**kw):
+                src = workload.make_inputs(cfg, seed=seed, device=dev)
+                layer = sd.SparseDLayer(cfg.T, 0.0, cfg.bq, cfg.bk, cfg.rho, **kw)
+                evs = []
+                for t in range(cfg.T):
+                    qq, kk, vv = src.rounded()
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    layer.step(qq, kk, vv, t, out=out)
+                    b.record()
+                    evs.append((a, b))
+                    src.advance()
+                torch.cuda.synchronize()
+                return sum(a.elapsed_time(b) for a, b in evs), layer
+
+            total, layer = run_schedule(n_dense=cfg.n_dense)
             rec["schedule"] = {"T": cfg.T, "n_dense": cfg.n_dense, "total_attention_ms": total, "dense_only_ms": cfg.T * dense_ms,
                                "speedup_measured": cfg.T * dense_ms / total,
                                "expected_if_sparse_as_efficient_as_dense":
                                    cfg.T / (cfg.n_dense + (cfg.T - cfg.n_dense) * keep / cfg.nkb + select_ms / dense_ms),
                                "calls": layer.calls}
+            # the paper's ablation rows (Table 2) on the same kernels: sparse from the first step, and a fresh
+            # selection at every sparse step (no handed-over statistics: the one-pass selection)
+            for mode, kw in (("no_skipping", {"n_dense": 0}),
+                             ("no_sparse_reusing", {"n_dense": cfg.n_dense, "reselect_every_step": True})):
+                ms, lay = run_schedule(**kw)
+                rec["schedule"][mode] = {"total_attention_ms": ms, "calls": lay.calls}
         block[name] = rec
         del inp, q, k, v, out, lse, ws, index
         print(f"[bench] workload {name} done", file=sys.stderr, flush=True)

@@ -256,6 +256,14 @@ def test_select_one_pass_re_references_rows_whose_logits_climb(bq, bk, L, D):
     _say(f"re-reference {bq}x{bk} L={L}: logit span {logit_span:.0f}, pooled rel err {rel.max():.2e}, rows checked {int(rows_ok.sum())}")
 
 
+def test_select_one_pass_closing_pass_in_several_segments():
+    """625 key blocks per row at head dim 64 with 128-row query blocks: the closing pass of the one-pass kernel
+    (row weights applied, rows summed) works through the key blocks in segments of 512 here."""
+    bq, bk, L, D, rho = 128, 32, 20000, 64, 0.02
+    q, k, _ = _rand_qkv(1, 1, 1, L, D, torch.bfloat16, seed=5, scale=0.5)
+    _check_selection(q, k, bq, bk, rho, False, "select one pass, 625 key blocks, D=64")
+
+
 def test_select_ties_resolve_to_lower_block_index():
     # Q = 0 makes every pooled score exactly 1/L: the kept set must be the first k blocks
     q = torch.zeros(1, 2, 512, 128, dtype=torch.bfloat16)
