@@ -24,17 +24,17 @@ namespace sparsed {
 
 namespace {
 
-[[maybe_unused]] constexpr int kChunk = 16;    // block sums staged per row before they go to the slab (64 contiguous bytes per row)
-[[maybe_unused]] constexpr int kChunkLd = 20;  // floats per staged row: 16 + padding that keeps 16-byte alignment and spreads the banks
+[[maybe_unused]] constexpr int kChunk = 8;    // block sums staged per row before they go to the slab (32 contiguous bytes per row)
+[[maybe_unused]] constexpr int kChunkLd = 8;  // floats per staged row (no padding: one staging store per key block is too rare for its bank conflicts to count)
 [[maybe_unused]] constexpr float kOverflow = 1.2676506e30f;  // 2^100: a 32-key partial sum at or above this triggers the re-reference path
 
-// Work-groups per compute unit the kernel is built for (LDS: two K tiles + staging), by waves per work-group.
-constexpr int groups_per_cu(int NW) { return NW >= 4 ? 3 : 3; }
+// Work-groups per compute unit the kernel is built for: two K tiles + staging is just under a quarter of the LDS.
+constexpr int groups_per_cu(int) { return 4; }
 
 }  // namespace
 
 template <int D, int NW, int BK>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 3 : NW >= 2 ? 2 : 1, NW >= 4 ? 3 : NW >= 2 ? 2 : 1)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 4 : NW >= 2 ? 2 : 1, NW >= 4 ? 4 : NW >= 2 ? 2 : 1)))
 void pool1p_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NT = NW * 64, QT = 32 * NW;
@@ -129,11 +129,8 @@ void pool1p_bf16_kernel(const PoolArgs a) {
       if (g == 0) chunk[wave][j][slot] = e;
       if (slot == kChunk - 1 || J == nkb_here - 1) {
         const int r = lane >> 1, half = lane & 1;
-        const u32x4 w0 = *reinterpret_cast<const u32x4*>(&chunk[wave][r][half * 8]);
-        const u32x4 w1 = *reinterpret_cast<const u32x4*>(&chunk[wave][r][half * 8 + 4]);
-        float* dst = slab + (int64_t)r * ld + (J & ~(kChunk - 1)) + half * 8;
-        *reinterpret_cast<u32x4*>(dst) = w0;
-        *reinterpret_cast<u32x4*>(dst + 4) = w1;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(&chunk[wave][r][half * 4]);
+        *reinterpret_cast<u32x4*>(slab + (int64_t)r * ld + (J & ~(kChunk - 1)) + half * 4) = w;
       }
     };
     // Out of line: some 32-key partial sum overflowed the reference. Raise the reference of the rows concerned to
