@@ -435,6 +435,16 @@ def main():
                                         "kernel": "bf16 32x32x16 matrix instructions only, operands in registers"}
         for key, val in (("roofline", sparse_tf), ("roofline_dense", dense_tf), ("roofline_select", select_tf)):
             result[key]["frac_of_measured_rate_random_operands"] = val / rand_tf
+        # The vector unit on its own: what the softmax side (one fma, one exp2, one add per logit, plus the running
+        # maximum and the bf16 conversion in attention) costs if nothing else ran.
+        fma_g, exp_g = sd.probe_valu_f32("fma"), sd.probe_valu_f32("exp2")
+        logits = cfg.B * cfg.Hq * cfg.L * cfg.L
+        result["valu_rate_measured"] = {"unit": "1e9 lane-operations/s", "fma_f32": fma_g, "exp2_f32": exp_g,
+                                        "exp2_cost_in_fma": fma_g / exp_g,
+                                        "vector_only_ms": {"dense_3.5_ops_plus_exp_per_logit": logits * (3.5 / fma_g + 1.0 / exp_g) * 1e-6,
+                                                           "pooled_scores_2_ops_plus_exp_per_logit": logits * (2.0 / fma_g + 1.0 / exp_g) * 1e-6},
+                                        "matrix_only_ms_at_random_operand_rate": {"dense": f_dense / rand_tf * 1e-9,
+                                                                                  "pooled_scores": f_select / rand_tf * 1e-9}}
     under_profiler = "rocprof" in os.environ.get("LD_PRELOAD", "") or any(key.startswith("ROCPROF") for key in os.environ)
     if not args.no_clock and not under_profiler:
         result["shader_clock_mhz"] = {"at_published_peak": 2400,

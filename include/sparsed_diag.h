@@ -25,6 +25,16 @@ extern "C" {
 sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out,
                                        const sparsed_exec* ex);
 
+/*
+ * The rate this GPU sustains on one kind of fp32 vector instruction alone, in 1e9 lane-operations per
+ * second (64 per wave instruction): op 0 = fused multiply-add, op 1 = base-2 exponential. 8 waves on
+ * every compute unit issue `iters` x 64 independent instructions each (iters in [1, 1000000]). The
+ * softmax side of attention needs one exponential per logit (Sec. 3.1, Eq. 1); the ratio of the two
+ * rates says how many ordinary vector instructions that exponential displaces. SYNCHRONISES the
+ * stream. Needs ex->workspace of at least 512 KiB (SPARSED_ERR_WORKSPACE otherwise).
+ */
+sparsed_status sparsed_probe_valu_f32(int32_t op, int32_t iters, double* gops_out, const sparsed_exec* ex);
+
 #ifdef __cplusplus
 }
 #endif

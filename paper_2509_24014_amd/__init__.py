@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     index_validate,
     index_window_entries,
     probe_mfma_bf16,
+    probe_valu_f32,
     kept_blocks,
     load_library,
     n_dense_steps,

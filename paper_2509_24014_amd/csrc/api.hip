@@ -521,6 +521,33 @@ sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, d
   return SPARSED_OK;
 }
 
+sparsed_status sparsed_probe_valu_f32(int32_t op, int32_t iters, double* gops_out, const sparsed_exec* ex) {
+  if (!gops_out) return fail(SPARSED_ERR_NULL, "gops_out is NULL");
+  if (op != 0 && op != 1) return fail(SPARSED_ERR_RANGE, "op must be 0 (fma) or 1 (exp2)");
+  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
+  char* scratch = nullptr;
+  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "vector-unit rate probe", &scratch);
+  if (st != SPARSED_OK) return st;
+  hipStream_t s = stream_of(ex);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = launch_valu_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, op, s);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(t0, s);
+  if (e == hipSuccess) e = launch_valu_rate(reinterpret_cast<float*>(scratch), iters, op, s);
+  if (e == hipSuccess) e = hipEventRecord(t1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  if (e != hipSuccess) return hip_fail(e, "vector-unit rate probe");
+  // work-groups x waves x lanes x instructions per iteration
+  const double ops = (double)kProbeGroups * 8.0 * 64.0 * 64.0 * (double)iters;
+  *gops_out = ms > 0.f ? ops / ((double)ms * 1e6) : 0.0;
+  return SPARSED_OK;
+}
+
 const char* sparsed_status_string(sparsed_status s) {
   switch (s) {
     case SPARSED_OK: return "ok";

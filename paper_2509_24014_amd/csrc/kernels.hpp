@@ -137,6 +137,8 @@ __host__ __device__ inline int window_row_length(int I, int block_q, int block_k
 constexpr int kProbeGroups = 256;
 constexpr int kProbeFloats = kProbeGroups * 512;
 hipError_t launch_mfma_rate(float* scratch, int iters, int random_operands, hipStream_t s);
+// Vector-unit rate probe, same launch shape: each wave issues 64 fp32 instructions per iteration (op 0: fma, 1: exp2).
+hipError_t launch_valu_rate(float* scratch, int iters, int op, hipStream_t s);
 
 // Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).
 int dense_qtile_bf16(int L);

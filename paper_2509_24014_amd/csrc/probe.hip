@@ -1,4 +1,4 @@
-// Diagnostic: the rate the bf16 matrix cores sustain on this chip, measured with nothing but matrix
+// Diagnostics. First: the rate the bf16 matrix cores sustain on this chip, measured with nothing but matrix
 // instructions on register-resident operands. The chip lowers its clock under load and the amount
 // depends on how much the operand bits toggle: all-zero operands reach the published peak, operands
 // with random mantissas and signs (what real Q, K, V look like) settle well below it. That second
@@ -48,6 +48,41 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(float* out, int iters, i
     for (int x = 0; x < 16; ++x) s += acc[u][x];
   out[blockIdx.x * 512 + threadIdx.x] = s;
 #endif
+}
+
+// The vector unit alone: 64 independent fp32 instructions per wave and iteration on 16 register chains, either
+// fused multiply-adds or base-2 exponentials. The ratio of the two rates is what an exponential costs in units
+// of an ordinary vector instruction, the figure the softmax side of every kernel here is priced with.
+template <int OP>
+__global__ __launch_bounds__(512) void valu_rate_kernel(float* out, int iters) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = -0.5f - 0.001f * (float)((threadIdx.x + i) & 31);
+  const float m = 0.999f, b = -0.0005f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        // exp2 of a value in (-1, 0) is in (0.5, 1); its negative is again in (-1, -0.5): the chain stays in range
+        if (OP == 1) x[i] = -__builtin_amdgcn_exp2f(x[i]);  // the negation is a source modifier, not an instruction
+        else x[i] = __builtin_fmaf(x[i], m, b);
+      }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(x[i]));
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += x[i];
+  out[blockIdx.x * 512 + threadIdx.x] = s;
+#endif
+}
+
+hipError_t launch_valu_rate(float* scratch, int iters, int op, hipStream_t s) {
+  if (op == 1) hipLaunchKernelGGL(valu_rate_kernel<1>, dim3(kProbeGroups), dim3(512), 0, s, scratch, iters);
+  else hipLaunchKernelGGL(valu_rate_kernel<0>, dim3(kProbeGroups), dim3(512), 0, s, scratch, iters);
+  return hipGetLastError();
 }
 
 // 256 work-groups of 8 waves (two per SIMD on a 256-CU part); scratch must hold kProbeFloats floats.
