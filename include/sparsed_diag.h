@@ -35,6 +35,21 @@ sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, d
  */
 sparsed_status sparsed_probe_valu_f32(int32_t op, int32_t iters, double* gops_out, const sparsed_exec* ex);
 
+/*
+ * The matrix rate (TFLOP/s) of an attention-like instruction mix with nothing else in the way: the
+ * launch of sparsed_probe_mfma_bf16 with random operands, where every matrix instruction is
+ * accompanied by `vector_per_mfma` independent fp32 vector instructions (one of 0, 2, 3, 4, 5, 6, 8;
+ * every fourth an exp2, the rest fma) and, if lds_operands != 0, takes one operand from a 1 KiB LDS
+ * read issued one group earlier. The softmax between the two products of Eq. 1 costs the attention
+ * kernels about 5 vector instructions per matrix instruction and K, V reach the matrix cores through
+ * LDS, so (5, 1) is the ceiling for such a kernel on this chip: no dependencies, barriers or global
+ * loads are in this probe. SYNCHRONISES the stream. Needs ex->workspace of at least 512 KiB
+ * (SPARSED_ERR_WORKSPACE otherwise); SPARSED_ERR_RANGE for other values of vector_per_mfma or iters
+ * outside [1, 1000000].
+ */
+sparsed_status sparsed_probe_mix_bf16(int32_t vector_per_mfma, int32_t lds_operands, int32_t iters,
+                                      double* tflops_out, const sparsed_exec* ex);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = [
     "sparsed_attn_dense", "sparsed_select_pattern", "sparsed_attn_sparse", "sparsed_select_pattern_isolated",
     "sparsed_kept_blocks", "sparsed_n_dense_steps", "sparsed_select_workspace_bytes", "sparsed_index_validate",
     "sparsed_status_string", "sparsed_last_error", "sparsed_version",
-    "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16", "sparsed_probe_valu_f32",
+    "sparsed_index_fill_window", "sparsed_index_window_entries", "sparsed_probe_mfma_bf16", "sparsed_probe_valu_f32", "sparsed_probe_mix_bf16",
     "sparsed_select_pattern_isolated_tokens", "sparsed_select_tokens_workspace_bytes",
     "sparsed_select_pattern_static", "sparsed_select_workspace_min_bytes",
 ]
@@ -101,6 +101,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.sparsed_probe_mfma_bf16.restype = ctypes.c_int
     lib.sparsed_probe_valu_f32.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), E]
     lib.sparsed_probe_valu_f32.restype = ctypes.c_int
+    lib.sparsed_probe_mix_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), E]
+    lib.sparsed_probe_mix_bf16.restype = ctypes.c_int
     lib.sparsed_status_string.argtypes = [ctypes.c_int]
     lib.sparsed_status_string.restype = ctypes.c_char_p
     lib.sparsed_last_error.argtypes = []
@@ -329,6 +331,16 @@ def probe_valu_f32(op: str, iters: int = 20000) -> float:
     ws = torch.empty(512 * 1024, dtype=torch.uint8, device="cuda")
     ex = _Exec(_stream_ptr(None), ws.data_ptr(), ws.numel(), None, None, None, None)
     _check(load_library().sparsed_probe_valu_f32({"fma": 0, "exp2": 1}[op], iters, ctypes.byref(out), ctypes.byref(ex)))
+    return out.value
+
+
+def probe_mix_bf16(vector_per_mfma: int, lds_operands: bool, iters: int = 20000) -> float:
+    """sparsed_probe_mix_bf16: TFLOP/s of matrix instructions issued together with vector instructions (a quarter of them
+    exp2) and, optionally, LDS operand reads: the ceiling for an attention-like inner loop (diagnostic, synchronises)."""
+    out = ctypes.c_double(0.0)
+    ws = torch.empty(512 * 1024, dtype=torch.uint8, device="cuda")
+    ex = _Exec(_stream_ptr(None), ws.data_ptr(), ws.numel(), None, None, None, None)
+    _check(load_library().sparsed_probe_mix_bf16(int(vector_per_mfma), 1 if lds_operands else 0, iters, ctypes.byref(out), ctypes.byref(ex)))
     return out.value
 
 

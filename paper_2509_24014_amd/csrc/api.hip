@@ -548,6 +548,35 @@ sparsed_status sparsed_probe_valu_f32(int32_t op, int32_t iters, double* gops_ou
   return SPARSED_OK;
 }
 
+sparsed_status sparsed_probe_mix_bf16(int32_t vector_per_mfma, int32_t lds_operands, int32_t iters, double* tflops_out,
+                                      const sparsed_exec* ex) {
+  if (!tflops_out) return fail(SPARSED_ERR_NULL, "tflops_out is NULL");
+  const int v = vector_per_mfma;
+  if (!(v == 0 || v == 2 || v == 3 || v == 4 || v == 5 || v == 6 || v == 8))
+    return fail(SPARSED_ERR_RANGE, "vector_per_mfma must be one of 0, 2, 3, 4, 5, 6, 8");
+  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
+  char* scratch = nullptr;
+  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "instruction-mix rate probe", &scratch);
+  if (st != SPARSED_OK) return st;
+  hipStream_t s = stream_of(ex);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = launch_mix_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, v, lds_operands != 0, s);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(t0, s);
+  if (e == hipSuccess) e = launch_mix_rate(reinterpret_cast<float*>(scratch), iters, v, lds_operands != 0, s);
+  if (e == hipSuccess) e = hipEventRecord(t1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  if (e != hipSuccess) return hip_fail(e, "instruction-mix rate probe");
+  const double flops = (double)kProbeGroups * 8.0 * 32.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
+  *tflops_out = ms > 0.f ? flops / ((double)ms * 1e9) : 0.0;
+  return SPARSED_OK;
+}
+
 const char* sparsed_status_string(sparsed_status s) {
   switch (s) {
     case SPARSED_OK: return "ok";

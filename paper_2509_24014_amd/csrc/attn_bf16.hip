@@ -15,8 +15,9 @@
 //      vector:  online softmax of S(u)  ->  P(u), running max / sum
 // which are independent of each other; S and P are double-buffered in registers (even / odd
 // sub-steps) and the tile loop is unrolled by two so that the LDS buffer roles are static.
-// Softmax is online (running max / running sum per query, fp32); probabilities are rounded to
-// bf16 for the second matrix product; the output accumulator is fp32.
+// Softmax is online with a FIXED reference per query (the row maximum of the first sub-tile, not a
+// running maximum; see softmax_sub) and a running sum, fp32; probabilities are rounded to bf16 for
+// the second matrix product; the output accumulator is fp32.
 #include "kernels.hpp"
 #include "tile_bf16.hpp"
 
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(NW * 64)
   constexpr bool kHasV = MODE != Mode::kStats;
   constexpr int kKBytes = KLayout<D>::kTileBytes;
   constexpr int kVBytes = kHasV ? VLayout<D>::kTileBytes : 16;
-  constexpr float kLazyLog2 = 8.0f;
+  constexpr float kOverflow = 1.152921504606847e18f;  // 2^60: a 16-key partial sum at or above this re-references the row
   // Four separate LDS objects on purpose: the compiler tells accesses to different LDS variables
   // apart, so a copy in flight into one buffer does not hold up fragment reads from the others.
   __shared__ __attribute__((aligned(1024))) char kbuf0[kKBytes];
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(NW * 64)
   f32x16 o[NQ][D / 32];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    M[nq] = -1e30f;
+    M[nq] = 0.f;
     lsum[nq] = 0.f;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
@@ -187,66 +188,85 @@ __global__ __launch_bounds__(NW * 64)
 
   const float c = a.scale_log2;
 
-  // Online softmax of one 32-key sub-tile: s (fp32 logits) -> p (bf16), updates M / lsum, reports the
-  // factor by which the output accumulator has to be rescaled (1 unless the reference maximum moved).
+  // Softmax of one 32-key sub-tile against the row's reference M: s (fp32 logits) -> p (bf16) and this lane's
+  // share `part` of the row sum. The reference is NOT the running maximum: it is fixed by the first sub-tile
+  // (its row maximum) and every later probability is 2^(s c - M), whatever its size. fp32 and bf16 carry
+  // 2^+-126, the quotient O / l does not depend on the reference, and a logit far below it underflows only
+  // where it is negligible beside the first sub-tile's own terms; so no maximum is taken, no accumulator
+  // rescaled, as long as the probabilities stay below kOverflow. The caller tests `part` for that after the
+  // sub-step's instruction block (a branch inside it would cut the block the scheduling hints apply to) and
+  // calls re_reference for the rare sub-tile that fails.
   // masked: apply `valid`, the number of keys of this sub-tile that exist (32 or more = all, 0 or less =
   // none: a phantom tile or the empty half of a partial last block). Unmasked steps skip the 16 selects.
-  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&alpha)[NQ], bool& any_raise, const bool masked, int valid) {
-    any_raise = false;
+  auto mask_sub = [&](f32x16(&s)[NQ], int valid) {
+    const int mine = valid - 8 * g;  // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the sub-tile
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        if (16 * (x >> 3) + (x & 7) >= mine) s[nq][x] = -__builtin_inff();
+  };
+  auto exp_sub = [&](const f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&part)[NQ]) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      if (masked) {
-        // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the sub-tile
-        const int mine = valid - 8 * g;
-#pragma unroll
-        for (int x = 0; x < 16; ++x)
-          if (16 * (x >> 3) + (x & 7) >= mine) s[nq][x] = -__builtin_inff();
-      }
-      float mx = fmaxf(s[nq][0], s[nq][1]);
-#pragma unroll
-      for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][x]), s[nq][x + 1]);
-      mx = pair_max(mx);
-      // Lazy reference maximum: raised only when the sub-tile maximum exceeds it by more than
-      // kLazyLog2 (probabilities then stay below 2^kLazyLog2, harmless in fp32 / bf16).
-      const float cand = mx * c;
-      const bool raise = cand > M[nq] + kLazyLog2;
-      const float Mn = raise ? cand : M[nq];
-      alpha[nq] = raise ? __builtin_amdgcn_exp2f(M[nq] - Mn) : 1.0f;
-      any_raise = any_raise || (__builtin_amdgcn_ballot_w64(raise) != 0);
-      M[nq] = Mn;
-      float part = 0.f;
+      part[nq] = 0.f;
 #pragma unroll
       for (int m = 0; m < 2; ++m) {
         u32x4 pk;
 #pragma unroll
         for (int x = 0; x < 8; x += 2) {
-          const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x], c, -Mn)),
-                             __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x + 1], c, -Mn))};
+          const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x], c, -M[nq])),
+                             __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][8 * m + x + 1], c, -M[nq]))};
           if (kHasV) pk[x >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
           // The denominator is summed from the unrounded fp32 probabilities with plain adds: the row
           // log-sum-exp that pattern selection reuses needs it to ~1e-7, and the packed bf16 dot
           // instruction, one op cheaper, runs on the matrix pipe and stalls the MFMAs it overlaps.
-          part += two[0];
-          part += two[1];
+          part[nq] += two[0];
+          part[nq] += two[1];
         }
         if (kHasV) {
           // pin: the probabilities must exist HERE, inside the block that holds the matrix
-          // instructions, not be sunk by the compiler past the (rare) rescale branch that follows
+          // instructions, not be sunk by the compiler past the (rare) branch that follows
           asm volatile("" : "+v"(pk));
           p[nq][m] = __builtin_bit_cast(bf16x8, pk);
         }
       }
-      lsum[nq] = lsum[nq] * alpha[nq] + part;
-      asm volatile("" : "+v"(lsum[nq]));
+      asm volatile("" : "+v"(part[nq]));
     }
   };
-  auto rescale_output = [&](const float(&alpha)[NQ]) {
+  auto softmax_sub = [&](f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&part)[NQ], const bool masked, int valid) {
+    if (masked) mask_sub(s, valid);
+    exp_sub(s, p, part);
+  };
+  auto row_max = [&](const f32x16(&s)[NQ], int nq) -> float {
+    float mx = fmaxf(s[nq][0], s[nq][1]);
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
+    for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[nq][x]), s[nq][x + 1]);
+    return pair_max(mx) * c;
+  };
+  // true if some lane's 16-key partial sum left the range the fixed reference is good for (wave-uniform)
+  auto overflowed = [&](const float(&part)[NQ]) -> bool {
+    bool bad = false;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) bad = bad || !(part[nq] < kOverflow);
+    return __builtin_amdgcn_ballot_w64(bad) != 0;
+  };
+  // Out of line, practically never taken: raise the reference of every row to at least this sub-tile's maximum,
+  // bring what the row has accumulated (sum and output, including the product issued in this sub-step, whose
+  // probabilities had the old reference) to the new one, and redo the sub-tile's probabilities.
+  auto re_reference = [&](const f32x16(&s)[NQ], bf16x8(&p)[NQ][2], float(&part)[NQ]) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      const float Mn = fmaxf(M[nq], row_max(s, nq));
+      const float alpha = __builtin_amdgcn_exp2f(M[nq] - Mn);  // <= 1; exactly 1 where nothing changes
+      M[nq] = Mn;
+      lsum[nq] *= alpha;
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha[nq];
+        for (int x = 0; x < 16; ++x) o[nq][dt][x] *= alpha;
+    }
+    exp_sub(s, p, part);
   };
 
   // Tile step t (LDS parity P = t & 1) = sub-steps 2t+1 and 2t+2 of the 32-key pipeline.
@@ -258,6 +278,8 @@ __global__ __launch_bounds__(NW * 64)
   // keys are masked, so they add nothing, and the same branch-free step serves the whole list. MASKED
   // steps (the last few of a list) count the keys that exist in each sub-tile and use the copy that
   // knows about a partial last block; the others assume full, real tiles.
+#define SPARSED_ADD_PART \
+  _Pragma("unroll") for (int nq_ = 0; nq_ < NQ; ++nq_) lsum[nq_] += part[nq_];
 #define SPARSED_TILE_STEP(P, MASKED, T)                                                            \
   {                                                                                                \
     char* const kb_free = (P) ? kbuf1 : kbuf0;                                                     \
@@ -274,19 +296,20 @@ __global__ __launch_bounds__(NW * 64)
     const int valid_odd = !(MASKED) ? 32 : half_blocks ? half_keys(2 * (T) + 1) : keys_at((T), blk0) - 32;     \
     const int valid_even = !(MASKED) ? 32 : half_blocks ? half_keys(2 * (T) + 2) : keys_at((T) + 1, blk1);     \
     const int blk_new = col_at((T) + 4);                                                           \
-    float alpha[NQ];                                                                               \
-    bool any_raise;                                                                                \
+    float part[NQ];                                                                                \
     logits_sub<D, NQ, false>(kb_next, 0, kaddr, qf, s_even);                                       \
     if (kHasV) pv_sub<D, NQ, false>(vb_this, 0, vaddr, p_even, o);                                 \
-    softmax_sub(s_odd, p_odd, alpha, any_raise, (MASKED), valid_odd);                              \
+    softmax_sub(s_odd, p_odd, part, (MASKED), valid_odd);                                          \
     sched_substep_interleave<D, NQ, kHasV>();                                                      \
-    if (kHasV && any_raise) rescale_output(alpha);                                                 \
+    if (overflowed(part)) re_reference(s_odd, p_odd, part);                                        \
+    SPARSED_ADD_PART                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                             \
     logits_sub<D, NQ, false>(kb_next, 1, kaddr, qf, s_odd);                                        \
     if (kHasV) pv_sub<D, NQ, false>(vb_this, 1, vaddr, p_odd, o);                                  \
-    softmax_sub(s_even, p_even, alpha, any_raise, (MASKED), valid_even);                           \
+    softmax_sub(s_even, p_even, part, (MASKED), valid_even);                                       \
     sched_substep_interleave<D, NQ, kHasV>();                                                      \
-    if (kHasV && any_raise) rescale_output(alpha);                                                 \
+    if (overflowed(part)) re_reference(s_even, p_even, part);                                      \
+    SPARSED_ADD_PART                                                                               \
     blk0 = blk1;                                                                                   \
     blk1 = blk2;                                                                                   \
     blk2 = blk3;                                                                                   \
@@ -303,9 +326,14 @@ __global__ __launch_bounds__(NW * 64)
     logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
     logits_sub<D, NQ, true>(kbuf0, 1, kaddr, qf, s_odd);
     {
-      float alpha[NQ];
-      bool any_raise;
-      softmax_sub(s_even, p_even, alpha, any_raise, true, half_blocks ? half_keys(0) : keys_at(0, blk0));  // O is still zero: nothing to rescale
+      // the first sub-tile fixes the reference: its row maximum (it always holds a key that exists)
+      mask_sub(s_even, half_blocks ? half_keys(0) : keys_at(0, blk0));
+      float part[NQ];
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) M[nq] = fmaxf(row_max(s_even, nq), -1e30f);
+      exp_sub(s_even, p_even, part);
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) lsum[nq] = part[nq];
     }
     __syncthreads();  // everyone is done with K(0) before tile step 0 lets K(2) overwrite it
 
@@ -330,6 +358,7 @@ __global__ __launch_bounds__(NW * 64)
     }
   }
 #undef SPARSED_TILE_STEP
+#undef SPARSED_ADD_PART
 
   // Combine the two half-row sums, normalise, store. In the accumulator a lane holds 4 consecutive
   // output columns of ONE row at a time, so direct stores would be 8-byte pieces scattered over 32

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
   constexpr int NW = 2 * RW, NT = NW * 64, QT = 32 * RW;
   constexpr int kKBytes = KLayout<D>::kTileBytes, kVBytes = VLayout<D>::kTileBytes;
-  constexpr float kLazyLog2 = 8.0f;
+  constexpr float kOverflow = 1.152921504606847e18f;  // 2^60: a 16-key partial sum at or above this re-references the row
   __shared__ __attribute__((aligned(1024))) char kbuf0[kKBytes];
   __shared__ __attribute__((aligned(1024))) char kbuf1[kKBytes];
   __shared__ __attribute__((aligned(1024))) char vbuf0[kVBytes];
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
   const int last_blk = (L - 1) / unit;                 // last unit that exists
   const int tail_keys = L - last_blk * unit;           // keys in it
 
-  float M = -1e30f, lsum = 0.f;
+  float M = 0.f, lsum = 0.f;
   f32x16 o[1][D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -139,33 +139,24 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
 
   const float c = a.scale_log2;
 
-  // Online softmax of this wave's 32 keys of one tile (same arithmetic as the general kernel): s -> p,
-  // updates M / lsum, reports the factor the output accumulator has to be rescaled by.
-  auto softmax_half = [&](f32x16(&s)[1], float& alpha, bool& any_raise, const bool masked, int valid) {
-    if (masked) {
-      const int mine = valid - 8 * g;  // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the half
+  // Softmax of this wave's 32 keys of one tile against the row's fixed reference M (same arithmetic as the
+  // general kernel: the reference is set once, from the first tile, and a sub-tile whose probabilities leave
+  // the range that is good for is redone out of line): s -> p and this lane's share of the row sum.
+  auto mask_half = [&](f32x16(&s)[1], int valid) {
+    const int mine = valid - 8 * g;  // register x of lane (j, g) holds key 16*(x/8) + 8*g + x%8 of the half
 #pragma unroll
-      for (int x = 0; x < 16; ++x)
-        if (16 * (x >> 3) + (x & 7) >= mine) s[0][x] = -__builtin_inff();
-    }
-    float mx = fmaxf(s[0][0], s[0][1]);
-#pragma unroll
-    for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[0][x]), s[0][x + 1]);
-    mx = pair_max(mx);
-    const float cand = mx * c;
-    const bool raise = cand > M + kLazyLog2;
-    const float Mn = raise ? cand : M;
-    alpha = raise ? __builtin_amdgcn_exp2f(M - Mn) : 1.0f;
-    any_raise = __builtin_amdgcn_ballot_w64(raise) != 0;
-    M = Mn;
-    float part = 0.f;
+    for (int x = 0; x < 16; ++x)
+      if (16 * (x >> 3) + (x & 7) >= mine) s[0][x] = -__builtin_inff();
+  };
+  auto exp_half = [&](const f32x16(&s)[1], float& part) {
+    part = 0.f;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
       u32x4 pk;
 #pragma unroll
       for (int x = 0; x < 8; x += 2) {
-        const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[0][8 * m + x], c, -Mn)),
-                           __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][8 * m + x + 1], c, -Mn))};
+        const f32x2 two = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[0][8 * m + x], c, -M)),
+                           __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][8 * m + x + 1], c, -M))};
         pk[x >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
         part += two[0];
         part += two[1];
@@ -173,8 +164,36 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
       asm volatile("" : "+v"(pk));  // keep the probabilities inside the block that holds the matrix instructions
       p[0][m] = __builtin_bit_cast(bf16x8, pk);
     }
-    lsum = lsum * alpha + part;
-    asm volatile("" : "+v"(lsum));
+    asm volatile("" : "+v"(part));
+  };
+  auto row_max = [&](const f32x16(&s)[1]) -> float {
+    float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+    for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, s[0][x]), s[0][x + 1]);
+    return pair_max(mx) * c;
+  };
+  auto softmax_half = [&](f32x16(&s)[1], float& part, const bool masked, int valid) {
+    if (masked) mask_half(s, valid);
+    exp_half(s, part);
+  };
+  // Out of line, practically never taken: raise the reference to at least this tile's maximum, bring the
+  // row's sum and output to it, redo the tile's probabilities.
+  auto re_reference = [&](const f32x16(&s)[1], float& part) {
+    const float Mn = fmaxf(M, row_max(s));
+    const float alpha = __builtin_amdgcn_exp2f(M - Mn);  // <= 1; exactly 1 where nothing changes
+    M = Mn;
+    lsum *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) o[0][dt][x] *= alpha;
+    exp_half(s, part);
+  };
+  // keys of this wave's half that exist in tile T of the list, whose first block number is `first`
+  auto valid_in = [&](int T, int first) -> int {
+    const int tile0 = __builtin_amdgcn_readfirstlane(first);
+    return half_blocks ? (2 * T + kh < entries ? (tile0 == last_blk ? tail_keys : 32) : 0)
+                       : (tile0 > last_blk ? 0 : tile0 == last_blk ? tail_keys : kTileK) - 32 * kh;
   };
 
   // Tile step t (LDS parity P = t & 1). On entry: S(t) in S_CUR, K(t+1) in kbuf[1-P], V(t) in vbuf[P];
@@ -188,19 +207,13 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     copy_k(blk2, kb_free);                                                                         \
     copy_v(blk1, vb_free);                                                                         \
     const int blk_new = col_at((T) + 4);                                                           \
-    const int tile0 = __builtin_amdgcn_readfirstlane(blk0);                                        \
-    const int valid = !(MASKED) ? 32                                                               \
-                      : half_blocks ? (2 * (T) + kh < entries ? (tile0 == last_blk ? tail_keys : 32) : 0) \
-                                    : (tile0 > last_blk ? 0 : tile0 == last_blk ? tail_keys : kTileK) - 32 * kh; \
-    float alpha;                                                                                   \
-    bool any_raise;                                                                                \
+    const int valid = !(MASKED) ? 32 : valid_in((T), blk0);                                         \
+    float part;                                                                                    \
     logits_sub<D, 1, false>(kb_next, kh, kaddr, qf, S_NEXT);                                       \
-    softmax_half(S_CUR, alpha, any_raise, (MASKED), valid);                                        \
+    softmax_half(S_CUR, part, (MASKED), valid);                                                    \
     sched_substep_interleave<D, 1, false>();                                                       \
-    if (any_raise) {                                                                               \
-      _Pragma("unroll") for (int dt = 0; dt < D / 32; ++dt)                                        \
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) o[0][dt][x] *= alpha;                          \
-    }                                                                                              \
+    if (__builtin_amdgcn_ballot_w64(!(part < kOverflow)) != 0) re_reference(S_CUR, part);          \
+    lsum += part;                                                                                  \
     __builtin_amdgcn_sched_barrier(0);                                                             \
     pv_sub<D, 1, true>(vb_this, kh, vaddr, p, o);                                                  \
     blk0 = blk1;                                                                                   \
@@ -216,6 +229,13 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     copy_v(blk0, vbuf0);
     __syncthreads();
     logits_sub<D, 1, true>(kbuf0, kh, kaddr, qf, s_a);
+    {
+      // The first tile fixes the reference: the maximum over the keys of this wave's half that exist. A half
+      // with no such key (a short first block) starts from a floor that the first real key re-references.
+      f32x16 first[1] = {s_a[0]};
+      mask_half(first, valid_in(0, blk0));
+      M = fmaxf(row_max(first), -1e30f);
+    }
     __syncthreads();  // everyone is done with K(0) before step 0 lets K(2) overwrite it
 
     int t = 0;

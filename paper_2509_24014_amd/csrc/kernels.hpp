@@ -139,6 +139,9 @@ constexpr int kProbeFloats = kProbeGroups * 512;
 hipError_t launch_mfma_rate(float* scratch, int iters, int random_operands, hipStream_t s);
 // Vector-unit rate probe, same launch shape: each wave issues 64 fp32 instructions per iteration (op 0: fma, 1: exp2).
 hipError_t launch_valu_rate(float* scratch, int iters, int op, hipStream_t s);
+// Matrix instructions together with vector_per_mfma (0, 2, 3, 4, 5, 6 or 8) vector instructions each, a quarter of them
+// exp2, and optionally one LDS operand read each; same launch shape and matrix work as launch_mfma_rate.
+hipError_t launch_mix_rate(float* scratch, int iters, int vector_per_mfma, int lds_operands, hipStream_t s);
 
 // Rows per work-group the dense / stats kernels use for this L (0 if L is unsupported).
 int dense_qtile_bf16(int L);

@@ -330,7 +330,7 @@ __device__ __forceinline__ void sched_substep_interleave() {
   constexpr int kMfma = (HAS_V ? (D / 32) * 2 * NQ : 0) + (D / 16) * NQ;
   constexpr int kReads = (HAS_V ? (D / 32) * 2 * 2 : 0) + (D / 16);
   constexpr int kAhead = HAS_V ? 6 : 3;
-  constexpr int kValu = (HAS_V ? 72 : 66) * NQ;  // rough size of one sub-tile's softmax
+  constexpr int kValu = (HAS_V ? 58 : 50) * NQ;  // rough size of one sub-tile's softmax
   constexpr int kGroups = kMfma / G;
   constexpr int kValuPer = (kValu + kGroups - 1) / kGroups;
   constexpr int kReadsPer = (kReads - kAhead + kGroups - 1) / kGroups;

@@ -107,6 +107,8 @@ def test_argument_validation_rejects_before_any_launch():
     assert lib.sparsed_probe_mfma_bf16(1, 0, ctypes.byref(out), None) == 5                                       # iters
     assert lib.sparsed_probe_mfma_bf16(1, 10, None, None) == 1
     assert lib.sparsed_probe_mfma_bf16(1, 10, ctypes.byref(out), None) == 7                                       # workspace
+    assert lib.sparsed_probe_mix_bf16(7, 1, 10, ctypes.byref(out), None) == 5                                     # mix
+    assert lib.sparsed_probe_mix_bf16(5, 1, 10, ctypes.byref(out), None) == 7                                     # workspace
     assert lib.sparsed_probe_valu_f32(2, 10, ctypes.byref(out), None) == 5                                        # op
     assert lib.sparsed_probe_valu_f32(1, 0, ctypes.byref(out), None) == 5                                         # iters
     assert lib.sparsed_probe_valu_f32(1, 10, None, None) == 1
