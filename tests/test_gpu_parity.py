@@ -61,6 +61,53 @@ def test_dense_bf16_peaked_rows_and_large_logits():
     assert_output_close(got, want, torch.bfloat16, "dense bf16 peaked")
 
 
+def _climbing_qkv(L, D, H, seed):
+    """Rows whose logits run away from their first keys: along the keys the logits of even query rows climb by hundreds
+    of octaves (slowly at first, then by more than a tile can absorb), those of odd rows fall by as much."""
+    g = torch.Generator().manual_seed(seed)
+    q = 0.05 * torch.randn(1, H, L, D, generator=g)
+    k = 0.05 * torch.randn(1, H, L, D, generator=g)
+    sign = torch.where(torch.arange(L) % 2 == 0, 1.0, -1.0)
+    q[..., 0] = sign[None, None, :] * (8.0 + torch.rand(1, H, L, generator=g))
+    ramp = torch.linspace(0.0, 1.0, L) ** 2
+    k[..., 0] = (ramp * 40.0 * math.sqrt(D))[None, None, :] * (1.0 + 0.25 * torch.rand(1, H, L, generator=g))
+    # such rows put all their weight on one or two keys, so an output row is nearly a copy of a row of V, and the
+    # absolute bar of the parity gate is meant for values of order one: keep V there
+    v = 0.5 * torch.randn(1, H, L, D, generator=g)
+    return q.to(torch.bfloat16), k.to(torch.bfloat16), v.to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("L,D", [(1024, 128), (600, 64), (2048 + 40, 128)])
+def test_dense_bf16_rows_whose_logits_leave_the_first_tiles_range(L, D):
+    """The attention kernels measure every probability of a row against the maximum of its first 32 keys and only
+    re-reference a row when a probability leaves the range fp32 holds comfortably. Here that happens over and over
+    (even rows) or never while everything after the first tile underflows (odd rows); output and row
+    log-sum-exp must match the oracle all the same."""
+    q, k, v = _climbing_qkv(L, D, 2, seed=L + D)
+    span = float(q[..., 0].float().abs().max() * k[..., 0].float().max()) / math.sqrt(D)
+    assert span * 1.4427 > 400
+    lse = torch.empty(1, 2, L, dtype=torch.float32, device=DEV)
+    got = sd.attn_dense(*_dev(q, k, v), lse_out=lse)
+    assert_output_close(got, oracle.attn_dense(q, k, v), torch.bfloat16, "dense bf16, climbing and falling rows")
+    logits = q.double() @ k.double().transpose(-1, -2) / math.sqrt(D)
+    want = torch.logsumexp(logits, dim=-1)
+    # fp32 carries a value of size x (the logit in octaves, the reference, their sum with log2 of the row sum, the
+    # result in nats) to x * 2^-24 at each of those steps: the bar grows with the span
+    assert (lse.cpu().double() - want).abs().max() < 2e-5 + 1e-6 * span
+
+
+@pytest.mark.parametrize("bq,bk,L,D", [(128, 64, 1024, 128), (64, 64, 1024, 128), (32, 64, 512, 128), (64, 32, 600, 64), (128, 128, 1000, 128)])
+def test_sparse_bf16_rows_whose_logits_leave_the_first_tiles_range(bq, bk, L, D):
+    """The same for the block-sparse kernels: the listed blocks lie far apart, so from one listed block to the next
+    the logits jump by more than fp32 can exponentiate, in both directions."""
+    q, k, v = _climbing_qkv(L, D, 2, seed=bq + bk + L)
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    rp, ci = random_csr(1, 2, nqb, nkb, min(6, nkb), seed=L + bq, device=DEV)
+    got = sd.attn_sparse(*_dev(q, k, v), sd.BlockIndex(rp, ci, bq, bk, nkb))
+    want = oracle.attn_sparse(q, k, v, rp.cpu().numpy(), ci.cpu().numpy(), bq, bk)
+    assert_output_close(got, want, torch.bfloat16, f"sparse bf16 {bq}x{bk}, climbing and falling rows")
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,L,D", [(1, 2, 2, 256, 64), (1, 2, 1, 96, 128), (2, 2, 2, 192, 64)])
 def test_dense_f32(B, Hq, Hkv, L, D):
     _say(f"dense f32 B={B} Hq={Hq} Hkv={Hkv} L={L} D={D}")
