@@ -329,8 +329,10 @@ __device__ __forceinline__ void sched_substep_interleave() {
   constexpr int G = 1;  // matrix instructions per group (coarser groups measured no better)
   constexpr int kMfma = (HAS_V ? (D / 32) * 2 * NQ : 0) + (D / 16) * NQ;
   constexpr int kReads = (HAS_V ? (D / 32) * 2 * 2 : 0) + (D / 16);
-  constexpr int kAhead = HAS_V ? 6 : 3;
-  constexpr int kValu = (HAS_V ? 58 : 50) * NQ;  // rough size of one sub-tile's softmax
+  constexpr int kAhead = HAS_V ? 4 : 3;
+  // vector instructions handed out between the matrix instructions: three after each of the 16 of an attention
+  // sub-step at head dim 128 (of 58; the rest follow the last one: measured better than four after each), otherwise all
+  constexpr int kValu = (HAS_V ? (D >= 128 ? 48 : 58) : 50) * NQ;
   constexpr int kGroups = kMfma / G;
   constexpr int kValuPer = (kValu + kGroups - 1) / kGroups;
   constexpr int kReadsPer = (kReads - kAhead + kGroups - 1) / kGroups;
