@@ -433,18 +433,18 @@ def main():
         zero_tf, rand_tf = sd.probe_mfma_bf16(False), sd.probe_mfma_bf16(True)
         result["mfma_rate_measured"] = {"unit": "TFLOP/s", "zero_operands": zero_tf, "random_operands": rand_tf,
                                         "kernel": "bf16 32x32x16 matrix instructions only, operands in registers"}
-        # The same matrix instructions issued the way an attention loop issues them (5 vector instructions each, a
-        # quarter of them exp2, operands read from LDS) but with no dependencies, barriers or global loads: the ceiling
-        # for the attention kernels; and the pooling mix (7 vector instructions per matrix instruction: half the matrix
-        # work per exponential), for which the nearest probe setting is 6 and 8.
-        mix = {"mfma_plus_5_vector": sd.probe_mix_bf16(5, False), "mfma_plus_5_vector_plus_lds_operands": sd.probe_mix_bf16(5, True),
+        # The same matrix instructions issued the way an attention loop issues them (58 vector instructions per 16 matrix
+        # instructions, a quarter of them exp2: probe setting 4; operands read from LDS) but with no dependencies, barriers
+        # or global loads: the ceiling for the attention kernels; and the pooling mix (7 vector instructions per matrix
+        # instruction: half the matrix work per exponential), for which the nearest probe settings are 6 and 8.
+        mix = {"mfma_plus_4_vector": sd.probe_mix_bf16(4, False), "mfma_plus_4_vector_plus_lds_operands": sd.probe_mix_bf16(4, True),
                "mfma_plus_6_vector_plus_lds_operands": sd.probe_mix_bf16(6, True),
                "mfma_plus_8_vector_plus_lds_operands": sd.probe_mix_bf16(8, True)}
         result["mfma_rate_measured"]["attention_like_mix_random_operands"] = mix
         for key, val in (("roofline", sparse_tf), ("roofline_dense", dense_tf), ("roofline_select", select_tf)):
             result[key]["frac_of_measured_rate_random_operands"] = val / rand_tf
         for key, val in (("roofline", sparse_tf), ("roofline_dense", dense_tf)):
-            result[key]["frac_of_attention_mix_ceiling"] = val / mix["mfma_plus_5_vector_plus_lds_operands"]
+            result[key]["frac_of_attention_mix_ceiling"] = val / mix["mfma_plus_4_vector_plus_lds_operands"]
         result["roofline_select"]["frac_of_pooling_mix_ceiling"] = select_tf / (
             0.5 * (mix["mfma_plus_6_vector_plus_lds_operands"] + mix["mfma_plus_8_vector_plus_lds_operands"]))
         # The vector unit on its own: what the softmax side (one fma, one exp2, one add per logit, plus the running
