@@ -108,6 +108,71 @@ def test_sparse_bf16_rows_whose_logits_leave_the_first_tiles_range(bq, bk, L, D)
     assert_output_close(got, want, torch.bfloat16, f"sparse bf16 {bq}x{bk}, climbing and falling rows")
 
 
+def _climbing_sweep_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        bq = int(rng.choice([32, 64, 128]))
+        bk = int(rng.choice([32, 64, 128]))
+        Hkv = int(rng.choice([1, 2]))
+        Hq = Hkv * int(rng.choice([1, 2]))
+        L = int(rng.integers(40, 1500))
+        short = int(rng.integers(1, L + 1))            # a second batch element that stops earlier
+        cases.append((i, Hq, Hkv, L, short, D, bq, bk))
+    return cases
+
+
+@pytest.mark.parametrize("case", _climbing_sweep_cases(16, seed=4242),
+                         ids=lambda c: f"{c[0]}-H{c[1]}/{c[2]}-L{c[3]}/{c[4]}-D{c[5]}-{c[6]}x{c[7]}")
+def test_sweep_rows_that_leave_the_first_tiles_range(case):
+    """Climbing and falling rows over random shapes: ragged lengths (partial last blocks and tiles), grouped heads,
+    two batch elements of different length, every query-block and key-block size; dense and sparse against the
+    oracle, the row log-sum-exp against its definition."""
+    _, Hq, Hkv, L, short, D, bq, bk = case
+    qs, ks, vs = [], [], []
+    for b in range(2):
+        q1, _, _ = _climbing_qkv(L, D, Hq, seed=case[0] * 7 + b)
+        _, k1, v1 = _climbing_qkv(L, D, Hkv, seed=case[0] * 7 + b + 100)
+        qs.append(q1), ks.append(k1), vs.append(v1)
+    q, k, v = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+    lens = torch.tensor([L, short], dtype=torch.int32)
+    qd, kd, vd = _dev(q, k, v)
+    lens_d = lens.to(DEV)
+    nqb, nkb = -(-L // bq), -(-L // bk)
+    lse = torch.zeros(2, Hq, L, dtype=torch.float32, device=DEV)
+    out = torch.zeros(2, Hq, L, D, dtype=torch.bfloat16, device=DEV)
+    sd.attn_dense(qd, kd, vd, out=out, lse_out=lse, seq_lens=lens_d)
+    rp, ci = random_csr(2, Hq, nqb, nkb, min(5, nkb), seed=case[0], device=DEV)
+    # the shorter sample's rows may only list blocks it has
+    nkb_s, nqb_s = -(-short // bk), -(-short // bq)
+    rp_h, ci_h = rp.cpu().numpy().copy(), ci.cpu().numpy().copy()
+    for h in range(Hq):
+        pos = 0
+        new_rp = np.zeros(nqb + 1, dtype=np.int32)
+        new_ci = np.full(ci_h.shape[2], -1, dtype=np.int32)
+        for I in range(nqb):
+            row = ci_h[1, h, rp_h[1, h, I]:rp_h[1, h, I + 1]]
+            row = row[row < nkb_s] if I < nqb_s else row[:0]
+            new_ci[pos:pos + len(row)] = row
+            pos += len(row)
+            new_rp[I + 1] = pos
+        rp_h[1, h], ci_h[1, h] = new_rp, new_ci
+    rp, ci = torch.from_numpy(rp_h).to(DEV), torch.from_numpy(ci_h).to(DEV)
+    outs = torch.zeros_like(out)
+    sd.attn_sparse(qd, kd, vd, sd.BlockIndex(rp, ci, bq, bk, nkb), out=outs, seq_lens=lens_d)
+    for b, n in enumerate((L, short)):
+        qb, kb, vb = q[b:b + 1, :, :n], k[b:b + 1, :, :n], v[b:b + 1, :, :n]
+        assert_output_close(out[b:b + 1, :, :n], oracle.attn_dense(qb, kb, vb), torch.bfloat16, f"dense, sample {b}")
+        logits = qb.double() @ kb.double().repeat_interleave(Hq // Hkv, 1).transpose(-1, -2) / math.sqrt(D)
+        span = float(logits.abs().max())
+        assert (lse[b:b + 1, :, :n].cpu().double() - torch.logsumexp(logits, dim=-1)).abs().max() < 2e-5 + 1e-6 * span
+        nq_b = -(-n // bq)
+        want = oracle.attn_sparse(qb, kb, vb, rp_h[b:b + 1, :, :nq_b + 1], ci_h[b:b + 1], bq, bk)
+        assert_output_close(outs[b:b + 1, :, :n], want, torch.bfloat16, f"sparse {bq}x{bk}, sample {b}")
+        assert (out[b, :, n:] == 0).all() and (outs[b, :, n:] == 0).all()      # rows past the length stay untouched
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,L,D", [(1, 2, 2, 256, 64), (1, 2, 1, 96, 128), (2, 2, 2, 192, 64)])
 def test_dense_f32(B, Hq, Hkv, L, D):
     _say(f"dense f32 B={B} Hq={Hq} Hkv={Hkv} L={L} D={D}")
