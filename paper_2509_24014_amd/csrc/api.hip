@@ -352,6 +352,35 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   return SPARSED_OK;
 }
 
+// The three machine probes share one shape: check the arguments, take 512 KiB of the caller's workspace, run a short
+// warm-up launch and a timed launch of `iters` iterations on the stream, return the timed launch's milliseconds.
+template <typename Launch>
+sparsed_status timed_probe(int32_t iters, const sparsed_exec* ex, const char* what, float* ms_out, Launch launch) {
+  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
+  char* scratch = nullptr;
+  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), what, &scratch);
+  if (st != SPARSED_OK) return st;
+  hipStream_t s = stream_of(ex);
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  hipError_t e = hipEventCreate(&t0);
+  if (e == hipSuccess) e = hipEventCreate(&t1);
+  if (e == hipSuccess) e = launch(reinterpret_cast<float*>(scratch), iters / 8 + 1, s);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(t0, s);
+  if (e == hipSuccess) e = launch(reinterpret_cast<float*>(scratch), iters, s);
+  if (e == hipSuccess) e = hipEventRecord(t1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(t1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  if (e != hipSuccess) return hip_fail(e, what);
+  *ms_out = ms;
+  return SPARSED_OK;
+}
+
+// matrix instructions of one probe launch: work-groups x waves x 32 per iteration, 2 * 32 * 32 * 16 FLOP each
+double probe_flops(int32_t iters) { return (double)kProbeGroups * 8.0 * 32.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0; }
+
 }  // namespace
 
 extern "C" {
@@ -497,51 +526,23 @@ int64_t sparsed_index_window_entries(int32_t seq_len, int32_t block_q, int32_t b
 
 sparsed_status sparsed_probe_mfma_bf16(int32_t random_operands, int32_t iters, double* tflops_out, const sparsed_exec* ex) {
   if (!tflops_out) return fail(SPARSED_ERR_NULL, "tflops_out is NULL");
-  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
-  char* scratch = nullptr;
-  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "matrix-core rate probe", &scratch);
-  if (st != SPARSED_OK) return st;
-  hipStream_t s = stream_of(ex);
-  hipEvent_t t0 = nullptr, t1 = nullptr;
-  hipError_t e = hipEventCreate(&t0);
-  if (e == hipSuccess) e = hipEventCreate(&t1);
-  if (e == hipSuccess) e = launch_mfma_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, random_operands, s);  // warm-up
-  if (e == hipSuccess) e = hipEventRecord(t0, s);
-  if (e == hipSuccess) e = launch_mfma_rate(reinterpret_cast<float*>(scratch), iters, random_operands, s);
-  if (e == hipSuccess) e = hipEventRecord(t1, s);
-  if (e == hipSuccess) e = hipEventSynchronize(t1);
   float ms = 0.f;
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
-  if (t0) (void)hipEventDestroy(t0);
-  if (t1) (void)hipEventDestroy(t1);
-  if (e != hipSuccess) return hip_fail(e, "matrix-core rate probe");
-  // waves x MFMAs per iteration x flops per 32x32x16 MFMA
-  const double flops = (double)kProbeGroups * 8.0 * 32.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
-  *tflops_out = ms > 0.f ? flops / ((double)ms * 1e9) : 0.0;
+  const sparsed_status st = timed_probe(iters, ex, "matrix-core rate probe", &ms, [&](float* scratch, int n, hipStream_t s) {
+    return launch_mfma_rate(scratch, n, random_operands, s);
+  });
+  if (st != SPARSED_OK) return st;
+  *tflops_out = ms > 0.f ? probe_flops(iters) / ((double)ms * 1e9) : 0.0;
   return SPARSED_OK;
 }
 
 sparsed_status sparsed_probe_valu_f32(int32_t op, int32_t iters, double* gops_out, const sparsed_exec* ex) {
   if (!gops_out) return fail(SPARSED_ERR_NULL, "gops_out is NULL");
   if (op != 0 && op != 1) return fail(SPARSED_ERR_RANGE, "op must be 0 (fma) or 1 (exp2)");
-  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
-  char* scratch = nullptr;
-  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "vector-unit rate probe", &scratch);
-  if (st != SPARSED_OK) return st;
-  hipStream_t s = stream_of(ex);
-  hipEvent_t t0 = nullptr, t1 = nullptr;
-  hipError_t e = hipEventCreate(&t0);
-  if (e == hipSuccess) e = hipEventCreate(&t1);
-  if (e == hipSuccess) e = launch_valu_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, op, s);  // warm-up
-  if (e == hipSuccess) e = hipEventRecord(t0, s);
-  if (e == hipSuccess) e = launch_valu_rate(reinterpret_cast<float*>(scratch), iters, op, s);
-  if (e == hipSuccess) e = hipEventRecord(t1, s);
-  if (e == hipSuccess) e = hipEventSynchronize(t1);
   float ms = 0.f;
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
-  if (t0) (void)hipEventDestroy(t0);
-  if (t1) (void)hipEventDestroy(t1);
-  if (e != hipSuccess) return hip_fail(e, "vector-unit rate probe");
+  const sparsed_status st = timed_probe(iters, ex, "vector-unit rate probe", &ms, [&](float* scratch, int n, hipStream_t s) {
+    return launch_valu_rate(scratch, n, op, s);
+  });
+  if (st != SPARSED_OK) return st;
   // work-groups x waves x lanes x instructions per iteration
   const double ops = (double)kProbeGroups * 8.0 * 64.0 * 64.0 * (double)iters;
   *gops_out = ms > 0.f ? ops / ((double)ms * 1e6) : 0.0;
@@ -554,26 +555,12 @@ sparsed_status sparsed_probe_mix_bf16(int32_t vector_per_mfma, int32_t lds_opera
   const int v = vector_per_mfma;
   if (!(v == 0 || v == 2 || v == 3 || v == 4 || v == 5 || v == 6 || v == 8))
     return fail(SPARSED_ERR_RANGE, "vector_per_mfma must be one of 0, 2, 3, 4, 5, 6, 8");
-  if (iters <= 0 || iters > 1000000) return fail(SPARSED_ERR_RANGE, "iters must be in [1, 1000000]");
-  char* scratch = nullptr;
-  const sparsed_status st = caller_workspace(ex, (size_t)kProbeFloats * sizeof(float), "instruction-mix rate probe", &scratch);
-  if (st != SPARSED_OK) return st;
-  hipStream_t s = stream_of(ex);
-  hipEvent_t t0 = nullptr, t1 = nullptr;
-  hipError_t e = hipEventCreate(&t0);
-  if (e == hipSuccess) e = hipEventCreate(&t1);
-  if (e == hipSuccess) e = launch_mix_rate(reinterpret_cast<float*>(scratch), iters / 8 + 1, v, lds_operands != 0, s);  // warm-up
-  if (e == hipSuccess) e = hipEventRecord(t0, s);
-  if (e == hipSuccess) e = launch_mix_rate(reinterpret_cast<float*>(scratch), iters, v, lds_operands != 0, s);
-  if (e == hipSuccess) e = hipEventRecord(t1, s);
-  if (e == hipSuccess) e = hipEventSynchronize(t1);
   float ms = 0.f;
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
-  if (t0) (void)hipEventDestroy(t0);
-  if (t1) (void)hipEventDestroy(t1);
-  if (e != hipSuccess) return hip_fail(e, "instruction-mix rate probe");
-  const double flops = (double)kProbeGroups * 8.0 * 32.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
-  *tflops_out = ms > 0.f ? flops / ((double)ms * 1e9) : 0.0;
+  const sparsed_status st = timed_probe(iters, ex, "instruction-mix rate probe", &ms, [&](float* scratch, int n, hipStream_t s) {
+    return launch_mix_rate(scratch, n, v, lds_operands != 0, s);
+  });
+  if (st != SPARSED_OK) return st;
+  *tflops_out = ms > 0.f ? probe_flops(iters) / ((double)ms * 1e9) : 0.0;
   return SPARSED_OK;
 }
 
