@@ -398,7 +398,22 @@ __global__ __launch_bounds__(64) void topk_kernel(const TopkArgs a) {
   }
 }
 
-// One work-group per head: exclusive scan of the row lengths, then every row copied to its place.
+// Exclusive scan over the 256 threads of a work-group (each brings the sum of its own consecutive rows): returns
+// this thread's offset, leaves the grand total in partial[255].
+__device__ __forceinline__ int scan_256(int sum, int32_t (&partial)[256], int tid) {
+  partial[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    const int add = tid >= off ? partial[tid - off] : 0;
+    __syncthreads();
+    partial[tid] += add;
+    __syncthreads();
+  }
+  return partial[tid] - sum;
+}
+
+// One work-group per head: exclusive scan of the row lengths into row_ptr, then the waves copy the rows to their
+// places, a wave per row and a lane per entry.
 __global__ __launch_bounds__(256) void compact_kernel(const CompactArgs a) {
   __shared__ int32_t partial[256];
   const int head = blockIdx.x, tid = threadIdx.x;
@@ -407,25 +422,21 @@ __global__ __launch_bounds__(256) void compact_kernel(const CompactArgs a) {
   const int32_t* counts = a.counts + (int64_t)head * a.nqb;
   int sum = 0;
   for (int I = first; I < last; ++I) sum += counts[I];
-  partial[tid] = sum;
-  __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {  // inclusive scan of the per-thread sums
-    const int add = tid >= off ? partial[tid - off] : 0;
-    __syncthreads();
-    partial[tid] += add;
-    __syncthreads();
-  }
-  int offset = partial[tid] - sum;
+  int offset = scan_256(sum, partial, tid);
   int32_t* rp = a.row_ptr + (int64_t)head * (a.nqb + 1);
   int32_t* ci = a.col_idx + (int64_t)head * a.cap_per_head;
   for (int I = first; I < last; ++I) {
-    const int n = counts[I];
-    const int32_t* src = a.rows_tmp + ((int64_t)head * a.nqb + I) * a.stride;
     rp[I] = offset;
-    for (int t = 0; t < n; ++t) ci[offset + t] = src[t];
-    offset += n;
+    offset += counts[I];
   }
   if (tid == 255) rp[a.nqb] = partial[255];
+  __syncthreads();  // the row pointer written above is visible to the whole work-group
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int I = wave; I < a.nqb; I += 4) {
+    const int beg = rp[I], n = rp[I + 1] - beg;
+    const int32_t* src = a.rows_tmp + ((int64_t)head * a.nqb + I) * a.stride;
+    for (int t = lane; t < n; t += 64) ci[beg + t] = src[t];
+  }
 }
 
 // ---------------------------------------------------------------------------- index validation
@@ -451,22 +462,32 @@ __global__ __launch_bounds__(256) void validate_kernel(const ValidateArgs a) {
 // ---------------------------------------------------------------------------- fixed patterns
 // Sliding window plus attention sinks as a block index (the fixed patterns the paper compares
 // against, Section 4.1): query block I keeps the leading `sink_blocks` key blocks and every key
-// block that holds a key within `half_window` tokens of one of its queries. One thread per row.
+// block that holds a key within `half_window` tokens of one of its queries. One work-group per head: row lengths
+// scanned into the row pointer, then a wave per row.
 __global__ __launch_bounds__(256) void window_index_kernel(const WindowArgs a) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= a.heads * a.nqb) return;
-  const int bh = r / a.nqb, I = r % a.nqb;
-  int offset = 0;
-  for (int i = 0; i < I; ++i) offset += window_row_length(i, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks);
-  int sink_end, first, last;
-  window_row_runs(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks, &sink_end, &first, &last);
+  __shared__ int32_t partial[256];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const int per = (a.nqb + 255) / 256;  // consecutive rows per thread
+  const int first_row = tid * per, last_row = first_row + per < a.nqb ? first_row + per : a.nqb;
+  int sum = 0;
+  for (int I = first_row; I < last_row; ++I) sum += window_row_length(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks);
+  int offset = scan_256(sum, partial, tid);
   int32_t* rp = a.row_ptr + (int64_t)bh * (a.nqb + 1);
-  int32_t* ci = a.col_idx + (int64_t)bh * a.cap_per_head + offset;
-  int n = 0;
-  for (int J = 0; J < sink_end; ++J) ci[n++] = J;
-  for (int J = first; J <= last; ++J) ci[n++] = J;
-  rp[I] = offset;
-  if (I == a.nqb - 1) rp[a.nqb] = offset + n;
+  int32_t* ci = a.col_idx + (int64_t)bh * a.cap_per_head;
+  for (int I = first_row; I < last_row; ++I) {
+    rp[I] = offset;
+    offset += window_row_length(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks);
+  }
+  if (tid == 255) rp[a.nqb] = partial[255];
+  __syncthreads();  // the row pointer written above is visible to the whole work-group
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int I = wave; I < a.nqb; I += 4) {  // a wave per row, a lane per entry: the sinks, then the window
+    int sink_end, first, last;
+    window_row_runs(I, a.block_q, a.block_k, a.L, a.half_window, a.sink_blocks, &sink_end, &first, &last);
+    int32_t* dst = ci + rp[I];
+    for (int J = lane; J < sink_end; J += 64) dst[J] = J;
+    for (int J = first + lane; J <= last; J += 64) dst[sink_end + J - first] = J;
+  }
 }
 
 // ---------------------------------------------------------------------------- launchers
@@ -527,9 +548,8 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_window_index(const WindowArgs& a, hipStream_t s) {
-  const int rows = a.heads * a.nqb;
-  if (rows <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(window_index_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, a);
+  if (a.heads <= 0 || a.nqb <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(window_index_kernel, dim3((unsigned)a.heads), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
