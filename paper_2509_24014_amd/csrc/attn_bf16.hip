@@ -348,6 +348,10 @@ __global__ __launch_bounds__(NW * 64)
       SPARSED_TILE_STEP(1, false, t + 1);
       t += 2;
     }
+    if (t + steady_reach - 1 < n) {  // room for one more unmasked step (t is even here): one masked step fewer
+      SPARSED_TILE_STEP(0, false, t);
+      t += 1;
+    }
     asm volatile("" : "+v"(lane_tail));
     for (; t < n; ++t) {
       if (t & 1) {

@@ -112,15 +112,22 @@ struct TileDma {
   static constexpr int kWaves = NT / 64;
   static constexpr int kPerWave = kWaveLoads / kWaves;
   static_assert(kWaveLoads % kWaves == 0, "tile must split evenly over the waves");
-  int32_t goff[kPerWave];  // byte offset of this lane's chunk within the global tile, per wave-load
+  // At head dim 128 one wave-load is four whole rows of the tile for K and for V alike, and a lane fetches the same
+  // chunk of its row in every wave-load: the loads of a wave differ by a uniform 4-row step, which rides in the
+  // scalar offset, and one per-lane offset serves them all (registers are what the attention kernels are short of).
+  // (Used where a wave issues four loads per tile, the 4-wave work-groups; with two the separate offsets measure faster.)
+  static constexpr bool kUniformStep = D == 128 && kPerWave >= 4;
+  int32_t goff[kUniformStep ? 1 : kPerWave];  // byte offset of this lane's chunk within the global tile, per wave-load
+  int32_t step;                               // kUniformStep: bytes between consecutive wave-loads of a wave
 
   __device__ static __forceinline__ int lds_piece_offset(int wl) {  // where KB number wl of the tile goes
     if (IS_V) return wl * 1024;
     return wl * KLayout<D>::kPieceBytes;
   }
   __device__ __forceinline__ void init(int64_t stride_l, int wave_in_group, int lane) {
+    step = (int32_t)(4 * stride_l * 2);
 #pragma unroll
-    for (int u = 0; u < kPerWave; ++u) {
+    for (int u = 0; u < (kUniformStep ? 1 : kPerWave); ++u) {
       int row, chunk;
       source_of(wave_in_group * kPerWave + u, lane, &row, &chunk);
       goff[u] = (int32_t)(row * stride_l * 2 + chunk * 16);
@@ -168,7 +175,7 @@ struct TileDma {
     init(stride_l, wave_in_group, lane);
     if (2 * wave_in_group * kPerWave >= kWaveLoads) {
 #pragma unroll
-      for (int u = 0; u < kPerWave; ++u) goff[u] -= (int32_t)(32 * stride_l * 2);
+      for (int u = 0; u < (kUniformStep ? 1 : kPerWave); ++u) goff[u] -= (int32_t)(32 * stride_l * 2);
     }
   }
   // the same for a 32-key block of which only the first `rows` rows exist (the last block of a sequence)
@@ -196,7 +203,8 @@ struct TileDma {
 #pragma unroll
     for (int u = 0; u < kPerWave; ++u) {
       char* dst = lds_tile + lds_piece_offset(wave_in_group * kPerWave + u);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, goff[u], tile_byte_offset, 0, 0);
+      if (kUniformStep) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, goff[0], tile_byte_offset + u * step, 0, 0);
+      else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SPARSED_LDS void*)dst, 16, goff[u], tile_byte_offset, 0, 0);
     }
   }
 };
