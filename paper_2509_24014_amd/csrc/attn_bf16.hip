@@ -145,10 +145,7 @@ __global__ __launch_bounds__(NW * 64)
     blk2 = col_at(2);
     blk3 = col_at(3);
   }
-  // Q after the block numbers: the loads complete in issue order, so the first K/V copies (which
-  // need blk0, blk1) can start while the Q rows are still on their way.
-  QFrag<D, NQ> qf;
-  qf.load(qbase, row0, L, a.q.sl, lane);
+  QFrag<D, NQ> qf;  // loaded after the first K/V copies have been issued (below)
   auto uni = [&](int v) -> int { return (MODE == Mode::kSparse) ? __builtin_amdgcn_readfirstlane(v) : v; };
   // keys that exist in tile number `tile` of the list (block `blk`): none past the end of the list
   auto keys_at = [&](int tile, int blk) -> int { return tile < n ? keys_of(uni(blk)) : 0; };
@@ -322,6 +319,11 @@ __global__ __launch_bounds__(NW * 64)
     copy_k_any(blk0, kbuf0, lane);
     copy_k_any(blk1, kbuf1, lane);
     if (kHasV) copy_v_any(blk0, vbuf0, lane);
+    // Q last: loads complete in issue order and the compiler's wait for a block number counts loads issued after it
+    // conservatively, so Q rows requested before the copies would have to ARRIVE before the copies could be issued
+    // (a second trip to memory in front of the first tiles: 1.2 us of a query block's own timeline, most of which the
+    // other work-group of the compute unit hides, so the launch as a whole gains little).
+    qf.load(qbase, row0, L, a.q.sl, lane);
     __syncthreads();
     logits_sub<D, NQ, true>(kbuf0, 0, kaddr, qf, s_even);
     logits_sub<D, NQ, true>(kbuf0, 1, kaddr, qf, s_odd);

@@ -108,8 +108,7 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     blk2 = col_at(2);
     blk3 = col_at(3);
   }
-  QFrag<D, 1> qf;
-  qf.load(qbase, row0, L, a.q.sl, lane);
+  QFrag<D, 1> qf;  // loaded after the first K/V copies have been issued (see attn_bf16.hip)
 
   const int64_t slab_rows = (int64_t)(a.L - 1);
   const __amdgpu_buffer_rsrc_t krsrc = make_rsrc(kbase, (slab_rows * a.k.sl + D) * 2);
@@ -227,6 +226,7 @@ __global__ __launch_bounds__(RW * 128) __attribute__((amdgpu_waves_per_eu(RW >= 
     copy_k(blk0, kbuf0);
     copy_k(blk1, kbuf1);
     copy_v(blk0, vbuf0);
+    qf.load(qbase, row0, L, a.q.sl, lane);
     __syncthreads();
     logits_sub<D, 1, true>(kbuf0, kh, kaddr, qf, s_a);
     {
