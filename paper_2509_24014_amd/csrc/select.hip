@@ -26,12 +26,14 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float x) {
   return x;
 }
 
-// One work-group (NW waves, 32 query rows each) per query block. Same 32-key software pipeline as
+// One work-group of NW waves, 32 query rows each, covers NW / QBW consecutive query blocks of QBW waves (one block
+// of 128 rows, two of 64 or four of 32 with NW = 4: small query blocks share the work-group's K tiles and keep four
+// waves on every SIMD). Same 32-key software pipeline as
 // the attention kernels: sub-step u interleaves the matrix work S(u+1) = K(u+1) Q^T with the vector
 // work of sub-tile u (p = 2^(s*c - lse), summed per lane). A key block is two sub-tiles; its
-// per-lane sums are reduced over the wave, then over the waves through LDS in a fixed order.
+// per-lane sums are reduced over the wave, then over the waves of its query block through LDS in a fixed order.
 // HALF: key blocks of 32 (the two 32-key sub-tiles of a tile are pooled separately).
-template <int D, int NW, bool HALF>
+template <int D, int NW, bool HALF, int QBW = NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 4 : NW >= 2 ? 2 : 1, NW >= 4 ? 4 : NW >= 2 ? 2 : 1)))
 void pool_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
@@ -45,11 +47,16 @@ void pool_bf16_kernel(const PoolArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 31;
+  static_assert(NW % QBW == 0, "whole query blocks per work-group");
+  constexpr int kBlocksPerGroup = NW / QBW, kBlockRows = 32 * QBW;
   const int lid = xcd_remap(blockIdx.x, gridDim.x);
-  const int I = lid % a.nqb;
-  const int bh = lid / a.nqb;
+  const int groups_per_head = (a.nqb + kBlocksPerGroup - 1) / kBlocksPerGroup;
+  const int gq = lid % groups_per_head;  // which run of 32 * NW rows of the head
+  const int bh = lid / groups_per_head;
   const int b = bh / a.Hq, h = bh % a.Hq;
   const int hk = h / (a.Hq / a.Hkv);
+  const int first_wave = (wave / QBW) * QBW;            // first wave of this wave's query block
+  const int I = gq * kBlocksPerGroup + wave / QBW;      // this wave's query block
 
   // length of this batch element (per-sample lengths shorten the whole-sequence key range with it)
   int L = a.L, key_len = a.key_len;
@@ -58,17 +65,19 @@ void pool_bf16_kernel(const PoolArgs a) {
     L = len < a.L ? len : a.L;
     key_len = L - a.key_begin < key_len ? L - a.key_begin : key_len;
   }
-  if (I * (32 * NW) >= L || key_len <= 0) return;  // uniform over the work-group
+  if (gq * (32 * NW) >= L || key_len <= 0) return;  // uniform over the work-group
   const __bf16* qbase = static_cast<const __bf16*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
   const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh + (int64_t)a.key_begin * a.k.sl;
-  const int row0 = I * (32 * NW) + wave * 32;
+  const int row0 = gq * (32 * NW) + wave * 32;
+  // a query block of the group that the head (or this sample) does not have: its waves run along with all-zero terms
+  const bool block_exists = I < a.nqb && I * kBlockRows < L;
 
   QFrag<D, 1> qf;
   qf.load(qbase, row0, L, a.q.sl, lane);
   // a query row past L (partial last query block) gets an infinite normaliser: all its terms are 0
   const float lse2 = (row0 + j < L) ? a.lse[(int64_t)bh * a.L + row0 + j] * 1.4426950408889634f : __builtin_inff();
   float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride + a.out_col0;
-  const int rows_here = (L - I * (32 * NW) < 32 * NW) ? L - I * (32 * NW) : 32 * NW;  // query rows that exist
+  const int rows_here = (L - I * kBlockRows < kBlockRows) ? L - I * kBlockRows : kBlockRows;  // query rows of the block that exist
   const int last_blk = (key_len - 1) / kTileK;
   const int tail_keys = key_len - last_blk * kTileK;  // keys that exist in the last key block of the range
   auto keys_of = [&](int blk) -> int { return blk == last_blk ? tail_keys : kTileK; };
@@ -106,16 +115,16 @@ void pool_bf16_kernel(const PoolArgs a) {
     return part;
   };
   const int tile_shift = a.block_k == 2 * kTileK ? 1 : 0;  // a 128-key block is pooled over two consecutive tiles
-  float block_acc = 0.f;                                   // thread 0: sum over the tiles of the block in progress
+  float block_acc = 0.f;                                   // first thread of a query block: sum over the tiles of the key block in progress
   auto flush_block = [&](int t, float part) {  // after the tile barrier: key tile t is complete
     (void)part;
-    if (tid == 0) {
+    if (tid == first_wave * 64 && block_exists) {
       if (HALF) {  // two 32-key blocks per tile; the second may not exist in the last tile
         float ev = 0.f, od = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          ev += wsum_even[t & 1][w];
-          od += wsum[t & 1][w];
+        for (int w = 0; w < QBW; ++w) {
+          ev += wsum_even[t & 1][first_wave + w];
+          od += wsum[t & 1][first_wave + w];
         }
         const int left = key_len - t * kTileK;  // keys from this tile's first on
         arow[2 * t] = ev * (1.0f / (float)(rows_here * (left < 32 ? left : 32)));
@@ -124,7 +133,7 @@ void pool_bf16_kernel(const PoolArgs a) {
       }
       float tot = block_acc;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) tot += wsum[t & 1][w];
+      for (int w = 0; w < QBW; ++w) tot += wsum[t & 1][first_wave + w];
       if ((t & tile_shift) == tile_shift || t == n - 1) {  // last tile of its key block
         const int J = t >> tile_shift;
         const int keys_here = key_len - J * a.block_k < a.block_k ? key_len - J * a.block_k : a.block_k;
@@ -493,23 +502,25 @@ __global__ __launch_bounds__(256) void window_index_kernel(const WindowArgs a) {
 // ---------------------------------------------------------------------------- launchers
 template <int D>
 static hipError_t launch_pool_bf16_d(int block_q, const PoolArgs& a, hipStream_t s) {
-  const int64_t total = (int64_t)a.B * a.Hq * a.nqb;
+  // every work-group is four waves = 128 consecutive rows of a head: one, two or four query blocks
+  if (block_q != 128 && block_q != 64 && block_q != 32) return hipErrorInvalidValue;
+  const int blocks_per_group = 128 / block_q;
+  const int64_t total = (int64_t)a.B * a.Hq * ((a.nqb + blocks_per_group - 1) / blocks_per_group);
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)total);
+  const dim3 grid((unsigned)total), block(256);
   switch (block_q) {
     case 128:
-      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 4, true>), grid, dim3(256), 0, s, a);
-      else hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false>), grid, dim3(256), 0, s, a);
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 4, true, 4>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false, 4>), grid, block, 0, s, a);
       break;
     case 64:
-      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 2, true>), grid, dim3(128), 0, s, a);
-      else hipLaunchKernelGGL((pool_bf16_kernel<D, 2, false>), grid, dim3(128), 0, s, a);
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 4, true, 2>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false, 2>), grid, block, 0, s, a);
       break;
     case 32:
-      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 1, true>), grid, dim3(64), 0, s, a);
-      else hipLaunchKernelGGL((pool_bf16_kernel<D, 1, false>), grid, dim3(64), 0, s, a);
+      if (a.block_k == 32) hipLaunchKernelGGL((pool_bf16_kernel<D, 4, true, 1>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((pool_bf16_kernel<D, 4, false, 1>), grid, block, 0, s, a);
       break;
-    default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
