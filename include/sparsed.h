@@ -255,7 +255,7 @@ int32_t sparsed_n_dense_steps(int32_t T, double skip);
 /*
  * Bytes of workspace the selection calls want for this q and these blocks (0 on bad arguments): the row statistics,
  * the pooled scores and, for bf16 inputs, the slabs of the one-pass pooled-score kernel that is used when no
- * ex->lse_in is handed over (block_q x nkb floats for each of a few hundred resident work-groups: 400 MB for 32
+ * ex->lse_in is handed over (128 x nkb floats for each of up to 1024 resident work-groups: 537 MB for 32
  * heads of 65536 tokens in 128 x 64 blocks). sparsed_select_workspace_min_bytes() is the part every call needs
  * (statistics + pooled scores, 75 MB in that example); with a workspace between the two, or with ex->lse_in set,
  * selection runs as row statistics (unless handed over) followed by pooled scores, two passes over the keys, with

@@ -136,7 +136,8 @@ size_t select_ws_bytes(int B, int Hq, int L, int nqb, int nkb) {
 // Scratch of the one-pass pooled-score kernel (bf16 inputs without a handed-over log-sum-exp): one slab of
 // block_q x (key blocks rounded up to 16) floats per persistent work-group.
 int onepass_slab_ld(int nkb) { return (nkb + 15) & ~15; }
-size_t onepass_slab_bytes(int bq, int nkb) { return align256((size_t)bq * onepass_slab_ld(nkb) * sizeof(float)); }
+// (a slab holds the 128 rows of a work-group whatever the query-block size)
+size_t onepass_slab_bytes(int nkb) { return align256((size_t)128 * onepass_slab_ld(nkb) * sizeof(float)); }
 constexpr int kOnepassMinGroups = 256;  // fewer slabs than compute units (and than pooled rows): the two-pass form is used instead
 
 // Extra scratch when the prefill boundary falls inside a key block: the two partial scores of that
@@ -254,10 +255,10 @@ sparsed_status select_impl(const sparsed_tensor* q, const sparsed_tensor* k, int
   p.out_col0 = 0;
   p.scale_log2 = scale_log2(q->D);
   hipError_t e = hipSuccess;
-  const size_t rows_total = (size_t)q->B * q->H * nqb;  // pooled rows = (head, query block) units
+  const size_t rows_total = (size_t)pool1p_units(q->B, q->H, nqb, bq);  // units of the one-pass kernel: 128 rows of a head each
   // How many one-pass slabs the scratch behind `need` has room for.
   const size_t ws_bytes = fixed_scratch ? fixed_scratch_bytes : ex->workspace_bytes;
-  const size_t slab_bytes = onepass_slab_bytes(bq, nkb);
+  const size_t slab_bytes = onepass_slab_bytes(nkb);
   size_t slabs = (ws_bytes - need) / slab_bytes;
   if (slabs > (size_t)pool1p_groups(bq)) slabs = (size_t)pool1p_groups(bq);
   if (slabs > rows_total) slabs = rows_total;
@@ -429,7 +430,7 @@ sparsed_status sparsed_select_pattern_isolated_tokens(const sparsed_tensor* q, c
 // slabs of the one-pass kernel, if these inputs can use it
 size_t onepass_bytes(const sparsed_tensor* q, int32_t block_q, int32_t nkb) {
   if (q->dtype != SPARSED_BF16 || (block_q != 32 && block_q != 64 && block_q != 128)) return 0;
-  return (size_t)pool1p_groups(block_q) * onepass_slab_bytes(block_q, nkb);
+  return (size_t)pool1p_groups(block_q) * onepass_slab_bytes(nkb);
 }
 
 size_t sparsed_select_tokens_workspace_bytes(const sparsed_tensor* q, int32_t block_q, int32_t block_k) {

@@ -110,6 +110,8 @@ hipError_t launch_pool_f32(int D, int block_q, const PoolArgs& a, hipStream_t s)
 // each with its own slab in a.slab. pool1p_groups: the number of work-groups that fills the chip for this block_q.
 hipError_t launch_pool1p_bf16(int D, int block_q, const PoolArgs& a, int groups, hipStream_t s);
 int pool1p_groups(int block_q);
+// Units of work of that launch: runs of 128 consecutive rows of one head (one, two or four query blocks).
+int64_t pool1p_units(int B, int Hq, int nqb, int block_q);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t s);
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t s);

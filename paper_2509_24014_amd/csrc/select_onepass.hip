@@ -5,9 +5,9 @@
 //
 // The normaliser Z_r of a query row is known only after its last key, so the per-row block sums
 // E[r, J] = sum_{j in J} exp(s_rj - m_r) are parked in a scratch slab that belongs to the work-group
-// (block_q x nkb floats: O(L) per work-group, never O(L^2) in total), and weighted by 1 / Z_r and summed
+// (128 x nkb floats: O(L) per work-group, never O(L^2) in total), and weighted by 1 / Z_r and summed
 // over the rows of the query block once the row is complete. Work-groups are persistent: each walks the
-// (head, query block) units wg, wg + G, ... and reuses its slab.
+// units (128 consecutive rows of a head: one, two or four query blocks) wg, wg + G, ... and reuses its slab.
 //
 // Reference m_r: the maximum logit of the row's first 32 keys. It is never above the row's true maximum, so
 // nothing underflows that the two-pass form (reference = log-sum-exp) would keep. A later logit more than
@@ -33,7 +33,9 @@ constexpr int groups_per_cu(int) { return 4; }
 
 }  // namespace
 
-template <int D, int NW, int BK>
+// QBW: waves per query block. A work-group is always NW = 4 waves = 128 consecutive rows of a head: one query block of
+// 128 rows, two of 64 or four of 32, which share its K tiles and its slab.
+template <int D, int NW, int BK, int QBW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 4 : NW >= 2 ? 2 : 1, NW >= 4 ? 4 : NW >= 2 ? 2 : 1)))
 void pool1p_bf16_kernel(const PoolArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (the body uses device-only types)
@@ -53,7 +55,10 @@ void pool1p_bf16_kernel(const PoolArgs a) {
   const int j = lane & 31, g = lane >> 5;
   const int ld = a.slab_ld;  // floats per slab row: nkb rounded up to a whole chunk
   float* const slab = a.slab + (int64_t)blockIdx.x * QT * ld + (int64_t)wave * 32 * ld;  // this wave's 32 rows
-  const int units = a.B * a.Hq * a.nqb;
+  static_assert(NW % QBW == 0, "whole query blocks per work-group");
+  constexpr int kBlocksPerGroup = NW / QBW, kBlockRows = 32 * QBW;
+  const int groups_per_head = (a.nqb + kBlocksPerGroup - 1) / kBlocksPerGroup;
+  const int units = a.B * a.Hq * groups_per_head;  // a unit: QT consecutive rows of one head
   const float c = a.scale_log2;
 
   TileDma<D, NT, false> kdma;
@@ -62,8 +67,8 @@ void pool1p_bf16_kernel(const PoolArgs a) {
   kaddr.init(lane);
 
   for (int unit = xcd_remap(blockIdx.x, gridDim.x); unit < units; unit += gridDim.x) {
-    const int I = unit % a.nqb;
-    const int bh = unit / a.nqb;
+    const int gq = unit % groups_per_head;
+    const int bh = unit / groups_per_head;
     const int b = bh / a.Hq, h = bh % a.Hq;
     const int hk = h / (a.Hq / a.Hkv);
     int L = a.L;  // length of this batch element
@@ -71,16 +76,14 @@ void pool1p_bf16_kernel(const PoolArgs a) {
       const int len = a.seq_lens[b];
       L = len < a.L ? len : a.L;
     }
-    if (I * QT >= L) continue;  // a query block this sample does not have (uniform over the work-group)
+    if (gq * QT >= L) continue;  // rows this sample does not have (uniform over the work-group)
     const int key_len = L;
     const __bf16* qbase = static_cast<const __bf16*>(a.q.ptr) + b * a.q.sb + h * a.q.sh;
     const __bf16* kbase = static_cast<const __bf16*>(a.k.ptr) + b * a.k.sb + hk * a.k.sh;
-    const int row0 = I * QT + wave * 32;
+    const int row0 = gq * QT + wave * 32;
 
     QFrag<D, 1> qf;
     qf.load(qbase, row0, L, a.q.sl, lane);
-    float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride;
-    const int rows_here = (L - I * QT < QT) ? L - I * QT : QT;  // query rows that exist
     const int last_blk = (key_len - 1) / kTileK;                 // last 64-key tile that exists
     const int tail_keys = key_len - last_blk * kTileK;           // keys in it
     const int n = last_blk + 1;
@@ -237,13 +240,20 @@ void pool1p_bf16_kernel(const PoolArgs a) {
         partial[wave * kSeg + x] = acc;
       }
       __syncthreads();
-      for (int x = tid; x < seg_n; x += NT) {
-        float tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) tot += partial[w * kSeg + x];
-        const int J = seg + x;
-        const int keys_here = key_len - J * BK < BK ? key_len - J * BK : BK;
-        arow[J] = tot * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
+      for (int qb = 0; qb < kBlocksPerGroup; ++qb) {  // the query blocks of the group, each summed over its own waves
+        const int I = gq * kBlocksPerGroup + qb;
+        if (I >= a.nqb || I * kBlockRows >= L) break;  // a block the head (or this sample) does not have
+        float* arow = a.apool + ((int64_t)bh * a.nqb + I) * a.out_stride;
+        const int rows_here = (L - I * kBlockRows < kBlockRows) ? L - I * kBlockRows : kBlockRows;  // query rows that exist
+        for (int x = tid; x < seg_n; x += NT) {
+          float tot = 0.f;
+#pragma unroll
+          for (int w = 0; w < QBW; ++w) tot += partial[(qb * QBW + w) * kSeg + x];
+          const int J = seg + x;
+          const int keys_here = key_len - J * BK < BK ? key_len - J * BK : BK;
+          arow[J] = tot * (1.0f / (float)(rows_here * keys_here));  // mean over the entries that exist
+        }
       }
       __syncthreads();  // the partial sums (and, after the last segment, the K buffers) may be overwritten
     }
@@ -251,37 +261,40 @@ void pool1p_bf16_kernel(const PoolArgs a) {
 #endif
 }
 
-int pool1p_groups(int block_q) {
-  const int nw = block_q / 32;
-  return 256 * groups_per_cu(nw);
+int pool1p_groups(int) { return 256 * groups_per_cu(4); }
+
+int64_t pool1p_units(int B, int Hq, int nqb, int block_q) {
+  const int per = 128 / block_q;  // query blocks per work-group
+  return (int64_t)B * Hq * ((nqb + per - 1) / per);
 }
 
-template <int D, int NW>
+template <int D, int QBW>
 static hipError_t launch_pool1p_bk(const PoolArgs& a, int groups, hipStream_t s) {
-  const dim3 grid((unsigned)groups), block(NW * 64);
+  const dim3 grid((unsigned)groups), block(256);
   switch (a.block_k) {
-    case 32: hipLaunchKernelGGL((pool1p_bf16_kernel<D, NW, 32>), grid, block, 0, s, a); break;
-    case 64: hipLaunchKernelGGL((pool1p_bf16_kernel<D, NW, 64>), grid, block, 0, s, a); break;
-    case 128: hipLaunchKernelGGL((pool1p_bf16_kernel<D, NW, 128>), grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL((pool1p_bf16_kernel<D, 4, 32, QBW>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((pool1p_bf16_kernel<D, 4, 64, QBW>), grid, block, 0, s, a); break;
+    case 128: hipLaunchKernelGGL((pool1p_bf16_kernel<D, 4, 128, QBW>), grid, block, 0, s, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 // One-pass pooled scores over the whole key range of every sample. a.slab holds `groups` slabs of
-// block_q x a.slab_ld floats; a.lse_out (optional) receives the row log-sum-exp.
+// 128 x a.slab_ld floats; a.lse_out (optional) receives the row log-sum-exp.
 hipError_t launch_pool1p_bf16(int D, int block_q, const PoolArgs& a, int groups, hipStream_t s) {
-  const int64_t units = (int64_t)a.B * a.Hq * a.nqb;
+  if (block_q != 128 && block_q != 64 && block_q != 32) return hipErrorInvalidValue;
+  const int64_t units = pool1p_units(a.B, a.Hq, a.nqb, block_q);
   if (units <= 0 || units > 0x7fffffff || groups < 1 || a.slab == nullptr || a.slab_ld < a.out_stride) return hipErrorInvalidValue;
   if (groups > units) groups = (int)units;
   if (D == 128) {
     if (block_q == 128) return launch_pool1p_bk<128, 4>(a, groups, s);
     if (block_q == 64) return launch_pool1p_bk<128, 2>(a, groups, s);
-    if (block_q == 32) return launch_pool1p_bk<128, 1>(a, groups, s);
+    return launch_pool1p_bk<128, 1>(a, groups, s);
   } else if (D == 64) {
     if (block_q == 128) return launch_pool1p_bk<64, 4>(a, groups, s);
     if (block_q == 64) return launch_pool1p_bk<64, 2>(a, groups, s);
-    if (block_q == 32) return launch_pool1p_bk<64, 1>(a, groups, s);
+    return launch_pool1p_bk<64, 1>(a, groups, s);
   }
   return hipErrorInvalidValue;
 }
